@@ -1,0 +1,278 @@
+"""CPU checker ("oracle") for the gradient bucket reduction stage.
+
+TEST INFRASTRUCTURE ONLY: used by the tests, by the smoke check and by the
+benchmark's CPU-baseline leg.  The GPU library never imports, links or calls
+anything in this directory, and nothing here imports the GPU package.
+
+What it computes (KAITIAN, Sec. III and III-C):
+
+* ``plan_shares``      -- per-device batch sizes b_i proportional to the device
+                          score, rounded to integers that sum to B_global
+                          (Sec. III-C, phase 2 and its display equation);
+* ``share_weights``    -- w_k = b_k / B, the weights under which per-device mean
+                          gradients combine into the global-batch mean;
+* ``assign_buckets``   -- which flat bucket each gradient tensor is copied into
+                          and at which element offset (the flattening DDP does
+                          before the gradient AllReduce, Sec. III);
+* ``pack``             -- bucket[off_t + i] = g_t[i];
+* ``weighted_reduce``  -- out[i] = sum_k w_k * x_k[i], ascending k;
+* ``unpack_scale``     -- g_t[i] = scale * bucket[off_t + i];
+* ``direct``           -- the same end result with no buckets at all:
+                          g_t[i] = scale * sum_k w_k g_t^(k)[i].
+
+Element arithmetic lives in ``kt_oracle.c`` (plain C, doubles); integer
+planning is plain Python below.  Arrays are numpy: float32 for fp32 data,
+uint16 raw bits for bf16 data.
+
+Parity pins: every function here is pinned by tests/test_oracle_*.py against
+closed forms, invariants, exact rational arithmetic, brute force on tiny
+inputs and library special cases; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from typing import Dict, List, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "kt_oracle.c")
+_LIB = os.path.join(_HERE, "libkt_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile kt_oracle.c with gcc (no fused contraction, no fast-math)."""
+    stale = (not os.path.exists(_LIB)
+             or os.path.getmtime(_LIB) < os.path.getmtime(_SRC))
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-std=c99", "-O2", "-ffp-contract=off", "-fno-fast-math",
+             "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _c():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        pp = ctypes.POINTER(ctypes.c_void_p)
+        i64, f32, vp = ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+        for name in ("kto_reduce_f32_D", "kto_reduce_f32_S",
+                     "kto_reduce_bf16_D", "kto_reduce_bf16_S"):
+            fn = getattr(lib, name)
+            fn.argtypes = [pp, vp, ctypes.c_int, i64, vp]
+            fn.restype = None
+        for name in ("kto_scale_f32", "kto_scale_bf16_D", "kto_scale_bf16_S"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, i64, f32, vp]
+            fn.restype = None
+        lib.kto_bf16_widen.argtypes = [ctypes.c_uint16]
+        lib.kto_bf16_widen.restype = ctypes.c_float
+        lib.kto_bf16_round.argtypes = [ctypes.c_double]
+        lib.kto_bf16_round.restype = ctypes.c_uint16
+        _lib = lib
+    return _lib
+
+
+# --------------------------------------------------------------------------
+# Sec. III-C: scores -> integer batch shares -> combine weights
+# --------------------------------------------------------------------------
+
+def plan_shares(thr: Sequence[float], B: int) -> List[int]:
+    """Integer batch shares b_i with b_i ~ score_i / sum_j score_j * B and
+    sum_i b_i = B (Sec. III-C display equation and the sentence after it).
+
+    ``thr`` are device throughputs (samples per unit time); score_i =
+    time_fastest / time_i = thr_i / max thr, and the common factor cancels in
+    score_i / sum_j score_j, so throughputs are used directly.
+
+    Reading of "rounded to the nearest integer, ensuring the sum matches":
+    largest remainder.  Take the floor of every quota, then give one extra
+    sample to the R = B - sum floor entries with the largest fractional parts
+    (ties to the lowest index).  Whenever plain rounding already sums to B
+    this is plain rounding.
+
+    Quotas are IEEE doubles: S = left-to-right sum, q_i = (thr_i / S) * B.
+    """
+    K = len(thr)
+    if K < 1 or B < 0 or B > (1 << 40):
+        raise ValueError("need K >= 1 and 0 <= B <= 2^40")
+    for t in thr:
+        if not (math.isfinite(t) and t > 0.0):
+            raise ValueError("throughputs must be finite and > 0")
+    S = 0.0
+    for t in thr:
+        S = S + float(t)
+    if not math.isfinite(S):
+        raise ValueError("throughput sum overflows")
+    q = [(float(t) / S) * float(B) for t in thr]
+    fl = [math.floor(x) for x in q]
+    frac = [x - f for x, f in zip(q, fl)]
+    b = [int(f) for f in fl]
+    R = B - sum(b)
+    if R < 0 or R > K:
+        raise ArithmeticError("remainder out of range")
+    order = sorted(range(K), key=lambda i: (-frac[i], i))
+    for i in order[:R]:
+        b[i] += 1
+    return b
+
+
+def share_weights(shares: Sequence[int], B: int) -> np.ndarray:
+    """w_k = b_k / B as one binary32 division of the two converted integers."""
+    if B <= 0:
+        raise ValueError("B must be positive to form weights")
+    return np.array([np.float32(b) / np.float32(B) for b in shares],
+                    dtype=np.float32)
+
+
+# --------------------------------------------------------------------------
+# Bucket layout (the flattening step of DDP's gradient AllReduce, Sec. III)
+# --------------------------------------------------------------------------
+
+def assign_buckets(numels: Sequence[int], elem_size: int, cap_bytes: int,
+                   align_bytes: int) -> Dict[str, List[int]]:
+    """Greedy bucket layout in the caller's tensor order.
+
+    Each tensor starts at the next multiple of ``align_bytes`` inside its
+    bucket.  A bucket is closed before a tensor whose (aligned) end would make
+    the bucket longer than ``cap_bytes``; tensors are never split, so a tensor
+    larger than the cap sits alone.  ``cap_bytes == 0`` means a single bucket.
+    A bucket's length is its last tensor's end rounded up to the alignment.
+    """
+    if elem_size not in (2, 4):
+        raise ValueError("elem_size")
+    if (align_bytes < elem_size or align_bytes % elem_size
+            or align_bytes & (align_bytes - 1) or align_bytes > 4096):
+        raise ValueError("align_bytes")
+    if cap_bytes < 0:
+        raise ValueError("cap_bytes")
+    A = align_bytes // elem_size
+
+    def up(x):
+        return (x + A - 1) // A * A
+
+    t_bucket, t_off = [], []
+    b_first, b_count, b_elems = [], [], []
+    cur_end = 0          # end (elements) of the last tensor in the open bucket
+    open_count = 0
+    for t, n in enumerate(numels):
+        if n < 0:
+            raise ValueError("numel")
+        start = up(cur_end)
+        if (open_count > 0 and cap_bytes > 0
+                and up(start + n) * elem_size > cap_bytes):
+            b_count.append(open_count)
+            b_elems.append(up(cur_end))
+            cur_end, open_count, start = 0, 0, 0
+        if open_count == 0:
+            b_first.append(t)
+        t_bucket.append(len(b_first) - 1)
+        t_off.append(start)
+        cur_end = start + n
+        open_count += 1
+    if open_count > 0:
+        b_count.append(open_count)
+        b_elems.append(up(cur_end))
+    return {"tensor_bucket": t_bucket, "tensor_offset": t_off,
+            "bucket_first": b_first, "bucket_count": b_count,
+            "bucket_elems": b_elems}
+
+
+# --------------------------------------------------------------------------
+# pack / reduce / unpack
+# --------------------------------------------------------------------------
+
+def _np_dtype(dtype: str):
+    return {"f32": np.float32, "bf16": np.uint16}[dtype]
+
+
+def pack(layout, tensors: Sequence[np.ndarray], dtype: str) -> List[np.ndarray]:
+    """bucket[off_t + i] = g_t[i]; every padding element is +0 (all bits 0).
+    Raw copies: bit patterns are preserved."""
+    nd = _np_dtype(dtype)
+    raw = np.uint32 if dtype == "f32" else np.uint16
+    buckets = [np.zeros(n, dtype=raw) for n in layout["bucket_elems"]]
+    for t, g in enumerate(tensors):
+        g = np.ascontiguousarray(g, dtype=nd).reshape(-1)
+        o = layout["tensor_offset"][t]
+        buckets[layout["tensor_bucket"][t]][o:o + g.size] = g.view(raw)
+    return [b.view(nd) for b in buckets]
+
+
+def weighted_reduce(peers: Sequence[np.ndarray], w: np.ndarray, dtype: str,
+                    mode: str = "D") -> np.ndarray:
+    """out[i] = sum_{k=0}^{K-1} w_k * x_k[i], ascending k (mode D: double
+    accumulation, one final rounding; mode S: binary32 product then fused
+    multiply-adds)."""
+    nd = _np_dtype(dtype)
+    K = len(peers)
+    if K < 1 or len(w) != K:
+        raise ValueError("K")
+    xs = [np.ascontiguousarray(p, dtype=nd).reshape(-1) for p in peers]
+    n = xs[0].size
+    if any(x.size != n for x in xs):
+        raise ValueError("peer sizes differ")
+    wv = np.ascontiguousarray(w, dtype=np.float32)
+    out = np.empty(n, dtype=nd)
+    ptrs = (ctypes.c_void_p * K)(*[x.ctypes.data for x in xs])
+    fn = getattr(_c(), "kto_reduce_%s_%s" % (dtype, mode))
+    fn(ptrs, wv.ctypes.data, K, n, out.ctypes.data)
+    return out
+
+
+def scale_array(x: np.ndarray, scale: float, dtype: str, mode: str = "D") -> np.ndarray:
+    nd = _np_dtype(dtype)
+    x = np.ascontiguousarray(x, dtype=nd).reshape(-1)
+    out = np.empty_like(x)
+    name = "kto_scale_f32" if dtype == "f32" else "kto_scale_bf16_" + mode
+    getattr(_c(), name)(x.ctypes.data, x.size, ctypes.c_float(scale), out.ctypes.data)
+    return out
+
+
+def unpack_scale(layout, buckets: Sequence[np.ndarray], numels: Sequence[int],
+                 scale: float, dtype: str, mode: str = "D") -> List[np.ndarray]:
+    """g_t[i] = scale * bucket[off_t + i]; padding is never read."""
+    out = []
+    for t, n in enumerate(numels):
+        o = layout["tensor_offset"][t]
+        b = buckets[layout["tensor_bucket"][t]]
+        out.append(scale_array(b[o:o + n], scale, dtype, mode))
+    return out
+
+
+def direct(peer_tensors: Sequence[Sequence[np.ndarray]], w: np.ndarray,
+           scale: float, dtype: str, mode: str = "D") -> List[np.ndarray]:
+    """The end result with no buckets: for every tensor t,
+    g_t = scale * sum_k w_k g_t^(k) (two roundings to the storage type, one
+    after the sum and one after the scale, like the bucketed path)."""
+    K = len(peer_tensors)
+    T = len(peer_tensors[0])
+    res = []
+    for t in range(T):
+        s = weighted_reduce([peer_tensors[k][t] for k in range(K)], w, dtype, mode)
+        res.append(scale_array(s, scale, dtype, mode))
+    return res
+
+
+# --------------------------------------------------------------------------
+# bf16 helpers (scalar, for tests)
+# --------------------------------------------------------------------------
+
+def bf16_widen(bits: int) -> float:
+    return float(_c().kto_bf16_widen(int(bits)))
+
+
+def bf16_round(x: float) -> int:
+    return int(_c().kto_bf16_round(float(x)))
+
+
+def bf16_to_f32_array(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of an array of bf16 bit patterns (numpy, no C)."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
