@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the gradient bucket hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic gradient set:
+  kt_bucket_pack         local gradients -> peer slot 0 of every bucket
+  kt_weighted_reduce     K peer copies of every bucket -> reduced bucket
+  kt_bucket_unpack_scale reduced buckets -> parameter gradients
+each as one batched launch over all buckets, on torch's current stream, with
+all inputs resident in HBM (peer slots 1..K-1 are filled before timing).
+
+Prints ONE JSON line: whole-step throughput in GB/s of algorithmic bytes
+((K + 5) * element size per element), the roofline figures of the dominant
+kernel (the reduce: (K + 1) * element size per element) measured with
+events around its launches inside the timed steps, and the CPU checker timed
+on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def setup(name, dev):
+    import torch
+    import paper_2505_10183_amd as kt
+    from paper_2505_10183_amd import workloads as wl
+
+    w = wl.WORKLOADS[name]
+    K = w.K
+    plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+    shares, weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
+    td = wl.torch_dtype(w.dtype)
+    nb = plan.num_buckets
+    elems = plan.bucket_elems()
+    peers = [[torch.empty(n, dtype=td, device=dev) for n in elems] for _ in range(K)]
+    # peer slots 1..K-1: other devices' gradients, packed by the same kernel
+    for k in range(1, K):
+        g = wl.gradient_set(w, k, dev)
+        plan.kt_bucket_pack(-1, g, peers[k])
+        torch.cuda.synchronize()
+        del g
+    local = wl.gradient_set(w, 0, dev)
+    outs = [torch.empty(n, dtype=td, device=dev) for n in elems]
+    result = [torch.empty_like(t) for t in local]
+    st = {
+        "w": w, "plan": plan, "K": K, "weights": weights, "shares": shares, "nb": nb,
+        "local": local, "peers": peers, "outs": outs, "result": result,
+        # pointer arrays marshalled once: the step itself only launches
+        "a_local": plan.marshal(local), "a_slot0": plan.marshal(peers[0]),
+        "a_peers": plan.marshal([peers[k][b] for b in range(nb) for k in range(K)]),
+        "a_outs": plan.marshal(outs), "a_result": plan.marshal(result),
+    }
+    import ctypes
+    st["a_w"] = (ctypes.c_float * K)(*weights)
+    return st
+
+
+def step(st, scale=1.0, ev=None):
+    p = st["plan"]
+    p.kt_bucket_pack(-1, st["a_local"], st["a_slot0"])
+    if ev is not None:
+        ev[0].record()
+    p.kt_weighted_reduce(-1, st["a_peers"], st["K"], st["a_w"], st["a_outs"])
+    if ev is not None:
+        ev[1].record()
+    p.kt_bucket_unpack_scale(-1, st["a_outs"], scale, st["a_result"])
+
+
+def time_workload(name, steps, warmup, dev):
+    import torch
+    st = setup(name, dev)
+    w = st["w"]
+    for _ in range(warmup):
+        step(st)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(st, ev=evs[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_step = (t1 - t0) * 1e3 / steps
+    ms_reduce = sum(a.elapsed_time(b) for a, b in evs) / steps
+    # pack and unpack alone, each over its own event-bracketed loop (context only)
+    p = st["plan"]
+
+    def loop(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(steps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / steps
+
+    ms_pack = loop(lambda: p.kt_bucket_pack(-1, st["a_local"], st["a_slot0"]))
+    ms_unpack = loop(lambda: p.kt_bucket_unpack_scale(-1, st["a_outs"], 1.0, st["a_result"]))
+    ms_reduce_alone = loop(lambda: p.kt_weighted_reduce(-1, st["a_peers"], st["K"], st["a_w"], st["a_outs"]))
+    e, s, K = w.total_elems, w.elem_size, st["K"]
+    res = {
+        "workload": name, "elements": e, "buckets": st["nb"], "K": K,
+        "ms_per_step": ms_step,
+        "step_GBps": (K + 5) * s * e / (ms_step * 1e-3) / 1e9,
+        "buckets_per_s": st["nb"] / (ms_step * 1e-3),
+        "reduce_ms_in_step": ms_reduce,
+        "reduce_GBps": (K + 1) * s * e / (ms_reduce * 1e-3) / 1e9,
+        "reduce_ms_alone": ms_reduce_alone,
+        "pack_ms": ms_pack, "pack_GBps": 2 * s * e / (ms_pack * 1e-3) / 1e9,
+        "unpack_ms": ms_unpack, "unpack_GBps": 2 * s * e / (ms_unpack * 1e-3) / 1e9,
+    }
+    return res, st
+
+
+def cpu_baseline(st, budget_elems):
+    """The CPU checker (as it stands, one thread) on the first buckets of the
+    same workload, same inputs: pack + reduce + unpack-scale once."""
+    import numpy as np
+    import oracle
+    from paper_2505_10183_amd import workloads as wl
+
+    w, plan, K = st["w"], st["plan"], st["K"]
+    nb = st["nb"]
+    chosen, total = [], 0
+    for b in range(nb):
+        n, first, cnt = plan.bucket_info(b)
+        if chosen and total + n > budget_elems:
+            break
+        chosen.append((b, n, first, cnt))
+        total += n
+    wts = oracle.share_weights(oracle.plan_shares(w.throughputs, w.global_batch), w.global_batch)
+    secs = 0.0
+    payload = 0
+    for b, n, first, cnt in chosen:
+        numels = w.numels[first:first + cnt]
+        lay = oracle.assign_buckets(numels, w.elem_size, 0, 16)
+        loc = [wl.to_host_array(st["local"][t]) for t in range(first, first + cnt)]
+        others = [wl.to_host_array(st["peers"][k][b]) for k in range(1, K)]
+        t0 = time.perf_counter()
+        slot0 = oracle.pack(lay, loc, w.dtype)[0]
+        red = oracle.weighted_reduce([slot0] + others, wts, w.dtype, "D")
+        oracle.unpack_scale(lay, [red], numels, 1.0, w.dtype, "D")
+        secs += time.perf_counter() - t0
+        payload += sum(numels)
+    gbps = (K + 5) * w.elem_size * payload / secs / 1e9
+    return {"value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "buckets 0..%d of %s (%d of %d elements), one pack+reduce+unpack pass, %.1f s"
+                      % (chosen[-1][0], w.name, payload, w.total_elems, secs)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="decoder_1p3b")
+    ap.add_argument("--also", default="vit_b16", help="comma list of further workloads reported for context")
+    ap.add_argument("--cpu-elems", type=int, default=0, help="element budget of the CPU baseline sample (0 = auto)")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU available", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    res, st = time_workload(args.workload, args.steps, args.warmup, dev)
+    w = st["w"]
+    cpu = None
+    if not args.no_cpu:
+        budget = args.cpu_elems or (300_000_000 if w.dtype == "bf16" else 900_000_000)
+        cpu = cpu_baseline(st, budget)
+    also = {}
+    del st
+    torch.cuda.empty_cache()
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        r, s2 = time_workload(name, args.steps, args.warmup, dev)
+        also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
+        del s2
+        torch.cuda.empty_cache()
+
+    line = {
+        "metric": "weighted bucket-reduce+pack/unpack HBM GB/s",
+        "value": round(res["step_GBps"], 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(res["ms_per_step"], 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "f32 accumulate, bf16 storage",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d tensors, %d elements %s, K=%d, B=%d, %d buckets (cap %d MiB)"
+                               % (w.name, len(w.shapes), w.total_elems, w.dtype, w.K, w.global_batch,
+                                  res["buckets"], w.bucket_cap_bytes >> 20),
+                   "launch": "one batched launch per kernel over all buckets",
+                   "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
+        "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
+        "buckets_per_s": round(res["buckets_per_s"], 1),
+        "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone"))},
+        "roofline": {"kernel": "kt_weighted_reduce (kt_reduce_kernel, K=%d, %s)" % (w.K, w.dtype),
+                     "bound": "hbm", "achieved": round(res["reduce_GBps"], 2), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4), "traffic": None},
+        "cpu_baseline": cpu,
+        "also": also,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,197 @@
+/*
+ * kt -- per-GPU reduction stage of a load-adaptive data-parallel step on
+ * AMD MI355X (gfx950).
+ *
+ * Setting (KAITIAN, Sec. III): under synchronous data parallelism every device
+ * computes gradients on its share of the global mini-batch; DDP flattens the
+ * per-parameter gradients into buckets and the K peer copies of each bucket are
+ * combined by the gradient AllReduce.  With the load-adaptive shares of
+ * Sec. III-C (b_i proportional to the device score, sum b_i = B_global) the
+ * devices hold means over different sample counts, so the copies combine with
+ * weights w_k = b_k / B into the global-batch mean.  This library is that
+ * stage on one GPU: plan shares, pack gradients into buckets, K-way weighted
+ * reduce, scale and unpack.  The K peer buffers are resident in device memory.
+ *
+ * Conventions
+ *  - Plain C ABI.  Every call returns a kt_status; on error the out-parameters
+ *    are untouched and kt_last_error() describes the failure (thread-local).
+ *  - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *    device memory owned by the caller, which must stay valid until the work
+ *    enqueued on the stream has finished.  The library owns only the plan.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Device calls are asynchronous: they enqueue kernels and return.
+ *  - Device calls use the calling thread's current HIP device; a plan binds to
+ *    the device of its first device call.
+ *  - Arrays indexed "by bucket" have kt_plan_num_buckets() entries and are
+ *    indexed by bucket id also when a single bucket is processed.  The whole
+ *    host array is copied on every call (all entries must be initialised;
+ *    NULL is fine for buckets not selected); only the selected buckets'
+ *    pointers are checked and dereferenced on the device.  Passing the same
+ *    array contents on successive calls lets the library reuse its resident
+ *    device copy instead of uploading it again.
+ */
+#ifndef KT_H
+#define KT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct kt_plan kt_plan;
+
+typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
+
+typedef enum {
+    KT_OK = 0,
+    KT_EINVAL = 1,        /* bad argument (NULL, range, non-finite, overlap)   */
+    KT_EALIGN = 2,        /* pointer not aligned to the element size           */
+    KT_ENOMEM = 3,        /* host or device allocation failed                  */
+    KT_EHIP = 4,          /* a HIP runtime call or kernel launch failed        */
+    KT_EUNSUPPORTED = 5   /* valid request outside the supported range         */
+} kt_status;
+
+#define KT_MAX_PEERS 64
+#define KT_ALL_BUCKETS (-1)
+
+/* Library version string, static storage. */
+const char *kt_version(void);
+
+/* Text for a status code, static storage. */
+const char *kt_status_string(kt_status s);
+
+/* Message of the last failing call on this thread, static storage ("" if none). */
+const char *kt_last_error(void);
+
+/*
+ * Load-adaptive batch shares (Sec. III-C, phase 2: the display equation and
+ * the rounding sentence after it).  Host only; touches no GPU.
+ *
+ *   thr[K]     host, in : device throughputs (samples per unit time), finite
+ *                         and > 0.  score_i = thr_i / max thr; the common
+ *                         factor cancels, so any positive scale is accepted.
+ *   B          in       : global batch size, 0 <= B <= 2^40.
+ *   shares[K]  host, out: integers b_i >= 0 with sum b_i = B.  Quota
+ *                         q_i = (thr_i / sum thr) * B in IEEE double
+ *                         (left-to-right sum); b_i = floor(q_i), then +1 for
+ *                         the B - sum floor entries with the largest
+ *                         fractional part, ties to the lowest index.
+ *   weights[K] host, out: optional (may be NULL).  w_k = (float)b_k /
+ *                         (float)B, one binary32 division; requires B > 0.
+ * Errors: KT_EINVAL for NULL thr/shares, K < 1, K > KT_MAX_PEERS, B out of
+ * range, a throughput that is not finite and positive, weights with B == 0.
+ */
+kt_status kt_plan_shares(const double *thr, int K, int64_t B,
+                         int64_t *shares, float *weights);
+
+/*
+ * Bucket plan: the flattening DDP applies before the gradient AllReduce
+ * (Sec. III).  Host only until the first device call, which uploads the
+ * plan's tables to the current device.
+ *
+ *   numel[T]     host, in: element count of each gradient tensor, >= 0, in the
+ *                          caller's order (kept).
+ *   T            in      : number of tensors, >= 0.
+ *   dt           in      : element type of tensors and buckets.
+ *   cap_bytes    in      : bucket size cap; 0 = one bucket.  A bucket closes
+ *                          before a tensor whose aligned end would exceed the
+ *                          cap; tensors are never split (an oversize tensor
+ *                          sits alone).
+ *   align_bytes  in      : every tensor starts at a multiple of this inside
+ *                          its bucket and the bucket length is rounded up to
+ *                          it.  Power of two, multiple of the element size,
+ *                          <= 4096.  16 gives the fast vector path; the
+ *                          element size gives dense packing.
+ *   out          out     : new plan, to be released with kt_plan_destroy.
+ * Errors: KT_EINVAL (arguments), KT_ENOMEM, KT_EUNSUPPORTED (the plan would
+ * need 2^31 or more 32 KiB tiles).
+ */
+kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt,
+                         int64_t cap_bytes, int align_bytes, kt_plan **out);
+
+/* Releases host tables and, if uploaded, the device tables (waits for the
+ * device to go idle first).  NULL is accepted. */
+kt_status kt_plan_destroy(kt_plan *plan);
+
+/* Number of buckets / tensors; -1 for a NULL plan. */
+int kt_plan_num_buckets(const kt_plan *plan);
+int kt_plan_num_tensors(const kt_plan *plan);
+
+/* Bucket b: length in elements (padding included; the caller allocates
+ * n_elems * element size bytes per bucket buffer), first tensor, tensor
+ * count.  Any out-pointer may be NULL. */
+kt_status kt_plan_bucket_info(const kt_plan *plan, int b, int64_t *n_elems,
+                              int *first_tensor, int *n_tensors);
+
+/* Tensor t: its bucket and element offset inside it.  Out-pointers may be NULL. */
+kt_status kt_plan_tensor_info(const kt_plan *plan, int t, int *bucket,
+                              int64_t *elem_offset);
+
+/*
+ * Tile table introspection (for checks).  The device kernels process a bucket
+ * in fixed tiles of 32 KiB, one workgroup each.  Tile i (0 <= i <
+ * kt_plan_num_tiles) covers elements [tile_in_bucket * E, min((tile_in_bucket
+ * + 1) * E, n_elems)) of `bucket`, E = 32768 / element size.  Tensors
+ * first_tensor .. first_tensor + n_tensors - 1 are the only ones that may own
+ * elements of the tile; n_tensors == 0 marks a tile wholly inside tensor
+ * first_tensor.  Out-pointers may be NULL.
+ */
+int64_t kt_plan_num_tiles(const kt_plan *plan);
+kt_status kt_plan_tile_info(const kt_plan *plan, int64_t i, int *bucket,
+                            int64_t *tile_in_bucket, int *first_tensor,
+                            int *n_tensors);
+
+/*
+ * Pack: bucket_b[off_t + i] = tensor_t[i] for every tensor of the selected
+ * bucket(s); padding elements are written as zero bits.  A raw copy: bit
+ * patterns are preserved.
+ *
+ *   bucket       in      : bucket id, or KT_ALL_BUCKETS for one batched launch.
+ *   tensor_ptrs  host, in: T device pointers (contiguous tensors), indexed by
+ *                          tensor id; entries of zero-size tensors may be NULL.
+ *   bucket_bufs  host, in: device pointers by bucket; only selected buckets
+ *                          are written on the device.
+ * Pointers must be aligned to the element size (KT_EALIGN otherwise); 16-byte
+ * aligned pointers take the vector path, others a slower correct one.
+ * Tensors and buckets must not overlap.
+ */
+kt_status kt_bucket_pack(kt_plan *plan, int bucket,
+                         const void *const *tensor_ptrs,
+                         void *const *bucket_bufs, void *stream);
+
+/*
+ * K-way weighted reduce: out_b[i] = sum_{k=0}^{K-1} w_k * peer_{b,k}[i] over
+ * the whole bucket length, evaluated per element in binary32 as
+ * acc = w_0 * x_0 (rounded product), then acc = fma(w_k, x_k, acc) for
+ * k = 1..K-1 in ascending k.  bf16 buckets are widened exactly, accumulated in
+ * binary32 and rounded to nearest-even once at the end.
+ *
+ *   peer_bufs  host, in: device pointers, entry [b * K + k] = peer k's copy of
+ *                        bucket b (num_buckets * K entries).
+ *   K          in      : 1 <= K <= KT_MAX_PEERS.
+ *   weights    host, in: K binary32 weights (copied during the call).
+ *   out_bufs   host, in: device pointers by bucket.  out_b may be identical to
+ *                        one peer_{b,k} (in place); any other overlap is an
+ *                        error where detected (equal ranges are; partial
+ *                        overlaps are undefined).
+ */
+kt_status kt_weighted_reduce(kt_plan *plan, int bucket,
+                             const void *const *peer_bufs, int K,
+                             const float *weights, void *const *out_bufs,
+                             void *stream);
+
+/*
+ * Unpack with scale: tensor_t[i] = scale * bucket_b[off_t + i] for every
+ * tensor of the selected bucket(s), one binary32 multiplication per element
+ * (bf16: widen, multiply, round to nearest-even).  Padding is not read into
+ * any tensor and nothing outside the tensors is written.
+ */
+kt_status kt_bucket_unpack_scale(kt_plan *plan, int bucket,
+                                 const void *const *bucket_bufs, float scale,
+                                 void *const *tensor_ptrs, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KT_H */

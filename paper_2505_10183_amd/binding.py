@@ -1,0 +1,188 @@
+"""Thin ctypes binding over libkt.so: argument marshalling only.
+
+Every step of the path (share planning, bucket layout, pack, reduce, unpack)
+runs inside the C-ABI library; this module converts Python lists / torch
+tensors to the pointers and sizes the C functions take and raises on a non-zero
+status.  There is no fallback: if the library is missing, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkt.so")
+
+KT_F32, KT_BF16 = 0, 1
+KT_ALL_BUCKETS = -1
+KT_MAX_PEERS = 64
+_DTYPES = {"f32": KT_F32, "bf16": KT_BF16}
+
+_lib = None
+
+
+class KtError(RuntimeError):
+    def __init__(self, status: int, name: str, msg: str):
+        super().__init__("%s: %s" % (name, msg))
+        self.status = status
+        self.status_name = name
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libkt.so is not built (%s); run __graft_entry__.build() or "
+                "python paper_2505_10183_amd/build.py" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        c = ctypes
+        vp, i64, i32 = c.c_void_p, c.c_int64, c.c_int
+        L.kt_version.restype = c.c_char_p
+        L.kt_status_string.restype = c.c_char_p
+        L.kt_status_string.argtypes = [i32]
+        L.kt_last_error.restype = c.c_char_p
+        L.kt_plan_shares.argtypes = [c.POINTER(c.c_double), i32, i64, c.POINTER(i64), c.POINTER(c.c_float)]
+        L.kt_plan_create.argtypes = [c.POINTER(i64), i32, i32, i64, i32, c.POINTER(vp)]
+        L.kt_plan_destroy.argtypes = [vp]
+        L.kt_plan_num_buckets.argtypes = [vp]
+        L.kt_plan_num_tensors.argtypes = [vp]
+        L.kt_plan_bucket_info.argtypes = [vp, i32, c.POINTER(i64), c.POINTER(i32), c.POINTER(i32)]
+        L.kt_plan_tensor_info.argtypes = [vp, i32, c.POINTER(i32), c.POINTER(i64)]
+        L.kt_plan_num_tiles.argtypes = [vp]
+        L.kt_plan_num_tiles.restype = i64
+        L.kt_plan_tile_info.argtypes = [vp, i64, c.POINTER(i32), c.POINTER(i64), c.POINTER(i32), c.POINTER(i32)]
+        L.kt_plan_tile_info.restype = i32
+        L.kt_bucket_pack.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), vp]
+        L.kt_weighted_reduce.argtypes = [vp, i32, c.POINTER(vp), i32, c.POINTER(c.c_float), c.POINTER(vp), vp]
+        L.kt_bucket_unpack_scale.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), vp]
+        for n in ("kt_plan_shares", "kt_plan_create", "kt_plan_destroy", "kt_plan_bucket_info",
+                  "kt_plan_tensor_info", "kt_bucket_pack", "kt_weighted_reduce", "kt_bucket_unpack_scale",
+                  "kt_plan_num_buckets", "kt_plan_num_tensors"):
+            getattr(L, n).restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(status: int):
+    if status != 0:
+        L = lib()
+        raise KtError(status, L.kt_status_string(status).decode(), L.kt_last_error().decode())
+
+
+def _ptr(x) -> int:
+    """Device address of a torch tensor, or an int address as is."""
+    if x is None:
+        return 0
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _ptr_array(items: Sequence) -> ctypes.Array:
+    arr = (ctypes.c_void_p * max(1, len(items)))()
+    for i, x in enumerate(items):
+        arr[i] = _ptr(x)
+    return arr
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> Tuple[List[int], Optional[List[float]]]:
+    """Integer batch shares (and optionally the combine weights w_k = b_k/B)."""
+    K = len(thr)
+    t = (ctypes.c_double * max(1, K))(*[float(x) for x in thr])
+    b = (ctypes.c_int64 * max(1, K))()
+    w = (ctypes.c_float * max(1, K))() if want_weights else None
+    _check(lib().kt_plan_shares(t, K, int(B), b, w))
+    return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
+
+
+class Plan:
+    """Owner of a kt_plan handle."""
+
+    def __init__(self, numels: Sequence[int], dtype: str, cap_bytes: int, align_bytes: int = 16):
+        self.dtype = dtype
+        self.numels = [int(n) for n in numels]
+        T = len(self.numels)
+        arr = (ctypes.c_int64 * max(1, T))(*self.numels)
+        h = ctypes.c_void_p()
+        _check(lib().kt_plan_create(arr, T, _DTYPES[dtype], int(cap_bytes), int(align_bytes), ctypes.byref(h)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            _check(lib().kt_plan_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def num_buckets(self) -> int:
+        return lib().kt_plan_num_buckets(self._h)
+
+    @property
+    def num_tensors(self) -> int:
+        return lib().kt_plan_num_tensors(self._h)
+
+    def bucket_info(self, b: int) -> Tuple[int, int, int]:
+        n, f, c = ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
+        _check(lib().kt_plan_bucket_info(self._h, b, ctypes.byref(n), ctypes.byref(f), ctypes.byref(c)))
+        return n.value, f.value, c.value
+
+    def tensor_info(self, t: int) -> Tuple[int, int]:
+        b, o = ctypes.c_int(), ctypes.c_int64()
+        _check(lib().kt_plan_tensor_info(self._h, t, ctypes.byref(b), ctypes.byref(o)))
+        return b.value, o.value
+
+    @property
+    def num_tiles(self) -> int:
+        return lib().kt_plan_num_tiles(self._h)
+
+    def tile_info(self, i: int) -> Tuple[int, int, int, int]:
+        b, k, f, c = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int(), ctypes.c_int()
+        _check(lib().kt_plan_tile_info(self._h, i, ctypes.byref(b), ctypes.byref(k), ctypes.byref(f), ctypes.byref(c)))
+        return b.value, k.value, f.value, c.value
+
+    def bucket_elems(self) -> List[int]:
+        return [self.bucket_info(b)[0] for b in range(self.num_buckets)]
+
+    # -- device calls: marshal pointers, call, raise on error ---------------
+
+    def marshal(self, items: Sequence) -> ctypes.Array:
+        """Pre-marshalled pointer array (reusable across calls)."""
+        return _ptr_array(items)
+
+    def _arr(self, items):
+        return items if isinstance(items, ctypes.Array) else _ptr_array(items)
+
+    def kt_bucket_pack(self, bucket: int, tensors, bucket_bufs, stream=None):
+        _check(lib().kt_bucket_pack(self._h, bucket, self._arr(tensors), self._arr(bucket_bufs), _stream(stream)))
+
+    def kt_weighted_reduce(self, bucket: int, peer_bufs, K: int, weights, out_bufs, stream=None):
+        """peer_bufs: flat sequence, entry [b * K + k]."""
+        if isinstance(weights, ctypes.Array):
+            w = weights
+        else:
+            w = (ctypes.c_float * max(1, len(weights)))(*[float(x) for x in weights])
+            if len(weights) != K:
+                raise ValueError("need K weights")
+        _check(lib().kt_weighted_reduce(self._h, bucket, self._arr(peer_bufs), K, w, self._arr(out_bufs),
+                                        _stream(stream)))
+
+    def kt_bucket_unpack_scale(self, bucket: int, bucket_bufs, scale: float, tensors, stream=None):
+        _check(lib().kt_bucket_unpack_scale(self._h, bucket, self._arr(bucket_bufs), float(scale),
+                                            self._arr(tensors), _stream(stream)))

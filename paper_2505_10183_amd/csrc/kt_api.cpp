@@ -1,0 +1,407 @@
+// C ABI of the library: plan objects, argument checks, per-call pointer tables
+// and kernel launches.  Host code; the kernels live in kt_kernels.hip.
+#include <hip/hip_runtime_api.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "kt_internal.h"
+
+// ---- error reporting -------------------------------------------------------
+
+static thread_local char g_err[512] = "";
+
+void kt_set_error(const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char *kt_last_error(void) { return g_err; }
+extern "C" const char *kt_version(void) { return "kt 0.1 (gfx950)"; }
+
+extern "C" const char *kt_status_string(kt_status s)
+{
+    switch (s) {
+    case KT_OK: return "KT_OK";
+    case KT_EINVAL: return "KT_EINVAL";
+    case KT_EALIGN: return "KT_EALIGN";
+    case KT_ENOMEM: return "KT_ENOMEM";
+    case KT_EHIP: return "KT_EHIP";
+    case KT_EUNSUPPORTED: return "KT_EUNSUPPORTED";
+    }
+    return "KT_?";
+}
+
+static kt_status hip_fail(const char *what, hipError_t e)
+{
+    kt_set_error("%s: %s", what, hipGetErrorString(e));
+    return e == hipErrorOutOfMemory ? KT_ENOMEM : KT_EHIP;
+}
+
+// ---- plan object -----------------------------------------------------------
+
+// A per-call table of device pointers (tensor/bucket or peer/out pointers)
+// lives in a small ring of device buffers.  A call whose pointers equal a
+// resident table reuses it, so a steady training loop uploads nothing.
+struct PtrSlot {
+    void *dev = nullptr;          // device copy
+    uint64_t *pinned = nullptr;   // pinned host staging of the same size
+    size_t cap = 0;               // capacity in entries
+    size_t n = 0;                 // entries in use
+    hipEvent_t uploaded = nullptr;
+    hipEvent_t last_use = nullptr;
+    hipStream_t upload_stream = nullptr;
+    hipStream_t use_stream = nullptr;
+    bool multi_stream = false;
+    bool valid = false;
+    uint64_t stamp = 0;
+};
+
+static const int KT_SLOTS = 8;
+
+struct kt_plan {
+    KtHostPlan hp;
+    std::mutex mu;
+    int device = -1;
+    void *dev_blob = nullptr;
+    KtDeviceTables tb{};
+    PtrSlot slots[KT_SLOTS];
+    uint64_t clock = 0;
+};
+
+extern "C" kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt, int64_t cap_bytes, int align_bytes,
+                                    kt_plan **out)
+{
+    if (!out) { kt_set_error("kt_plan_create: NULL out"); return KT_EINVAL; }
+    kt_plan *p = new (std::nothrow) kt_plan;
+    if (!p) { kt_set_error("kt_plan_create: out of host memory"); return KT_ENOMEM; }
+    const char *msg = "";
+    kt_status st;
+    try {
+        st = kt_build_host_plan(numel, T, dt, cap_bytes, align_bytes, p->hp, &msg);
+    } catch (const std::bad_alloc &) {
+        st = KT_ENOMEM; msg = "out of host memory";
+    }
+    if (st != KT_OK) {
+        kt_set_error("kt_plan_create: %s", msg);
+        delete p;
+        return st;
+    }
+    *out = p;
+    return KT_OK;
+}
+
+extern "C" kt_status kt_plan_destroy(kt_plan *p)
+{
+    if (!p) return KT_OK;
+    kt_status st = KT_OK;
+    if (p->device >= 0) {
+        int cur = -1;
+        (void)hipGetDevice(&cur);
+        if (cur != p->device) (void)hipSetDevice(p->device);
+        hipError_t e = hipDeviceSynchronize();
+        if (e != hipSuccess) st = hip_fail("kt_plan_destroy: hipDeviceSynchronize", e);
+        for (PtrSlot &s : p->slots) {
+            if (s.dev) (void)hipFree(s.dev);
+            if (s.pinned) (void)hipHostFree(s.pinned);
+            if (s.uploaded) (void)hipEventDestroy(s.uploaded);
+            if (s.last_use) (void)hipEventDestroy(s.last_use);
+        }
+        if (p->dev_blob) (void)hipFree(p->dev_blob);
+        if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
+    }
+    delete p;
+    return st;
+}
+
+extern "C" int kt_plan_num_buckets(const kt_plan *p) { return p ? (int)p->hp.b_elems.size() : -1; }
+extern "C" int kt_plan_num_tensors(const kt_plan *p) { return p ? (int)p->hp.t_numel.size() : -1; }
+
+extern "C" kt_status kt_plan_bucket_info(const kt_plan *p, int b, int64_t *n_elems, int *first_tensor, int *n_tensors)
+{
+    if (!p || b < 0 || b >= (int)p->hp.b_elems.size()) { kt_set_error("kt_plan_bucket_info: bad plan or bucket"); return KT_EINVAL; }
+    if (n_elems) *n_elems = p->hp.b_elems[b];
+    if (first_tensor) *first_tensor = p->hp.b_first[b];
+    if (n_tensors) *n_tensors = p->hp.b_count[b];
+    return KT_OK;
+}
+
+extern "C" kt_status kt_plan_tensor_info(const kt_plan *p, int t, int *bucket, int64_t *elem_offset)
+{
+    if (!p || t < 0 || t >= (int)p->hp.t_numel.size()) { kt_set_error("kt_plan_tensor_info: bad plan or tensor"); return KT_EINVAL; }
+    if (bucket) *bucket = p->hp.t_bucket[t];
+    if (elem_offset) *elem_offset = p->hp.t_off[t];
+    return KT_OK;
+}
+
+extern "C" int64_t kt_plan_num_tiles(const kt_plan *p) { return p ? (int64_t)p->hp.tiles.size() : -1; }
+
+extern "C" kt_status kt_plan_tile_info(const kt_plan *p, int64_t i, int *bucket, int64_t *tile_in_bucket,
+                                       int *first_tensor, int *n_tensors)
+{
+    if (!p || i < 0 || i >= (int64_t)p->hp.tiles.size()) { kt_set_error("kt_plan_tile_info: bad plan or tile"); return KT_EINVAL; }
+    const KtTile &tl = p->hp.tiles[(size_t)i];
+    if (bucket) *bucket = tl.bucket;
+    if (tile_in_bucket) *tile_in_bucket = tl.tile_in_bucket;
+    if (first_tensor) *first_tensor = tl.t0;
+    if (n_tensors) *n_tensors = tl.nt;
+    return KT_OK;
+}
+
+// Upload the plan tables on the first device call.  Caller holds p->mu.
+static kt_status ensure_device(kt_plan *p)
+{
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return hip_fail("hipGetDevice", e);
+    if (p->device >= 0) {
+        if (cur != p->device) { kt_set_error("plan is bound to device %d, current device is %d", p->device, cur); return KT_EINVAL; }
+        return KT_OK;
+    }
+    const KtHostPlan &hp = p->hp;
+    const size_t T = hp.t_numel.size(), nb = hp.b_elems.size(), nt = hp.tiles.size();
+    auto pad = [](size_t x) { return (x + 255) / 256 * 256; };
+    const size_t o_tiles = 0;
+    const size_t o_off = o_tiles + pad(nt * sizeof(KtTile));
+    const size_t o_numel = o_off + pad(T * 8);
+    const size_t o_belems = o_numel + pad(T * 8);
+    const size_t total = o_belems + pad(nb * 8) + 256;
+    std::vector<char> host(total, 0);
+    if (nt) memcpy(host.data() + o_tiles, hp.tiles.data(), nt * sizeof(KtTile));
+    if (T) memcpy(host.data() + o_off, hp.t_off.data(), T * 8);
+    if (T) memcpy(host.data() + o_numel, hp.t_numel.data(), T * 8);
+    if (nb) memcpy(host.data() + o_belems, hp.b_elems.data(), nb * 8);
+    void *blob = nullptr;
+    e = hipMalloc(&blob, total);
+    if (e != hipSuccess) return hip_fail("hipMalloc(plan tables)", e);
+    e = hipMemcpy(blob, host.data(), total, hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(blob); return hip_fail("hipMemcpy(plan tables)", e); }
+    char *d = static_cast<char *>(blob);
+    p->dev_blob = blob;
+    p->tb.tiles = reinterpret_cast<const KtTile *>(d + o_tiles);
+    p->tb.t_off = reinterpret_cast<const int64_t *>(d + o_off);
+    p->tb.t_numel = reinterpret_cast<const int64_t *>(d + o_numel);
+    p->tb.b_elems = reinterpret_cast<const int64_t *>(d + o_belems);
+    p->device = cur;
+    return KT_OK;
+}
+
+// Make `vals[0..n)` resident on the device for a launch on `stream`.
+// Caller holds p->mu.  On success *slot_out is the slot to mark after launch.
+static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipStream_t stream, PtrSlot **slot_out)
+{
+    hipError_t e;
+    PtrSlot *hit = nullptr, *victim = nullptr;
+    for (PtrSlot &s : p->slots) {
+        if (s.valid && s.n == n && memcmp(s.pinned, vals, n * 8) == 0) { hit = &s; break; }
+    }
+    if (hit) {
+        if (hit->upload_stream != stream) {
+            e = hipStreamWaitEvent(stream, hit->uploaded, 0);
+            if (e != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
+        }
+        hit->stamp = ++p->clock;
+        *slot_out = hit;
+        return KT_OK;
+    }
+    for (PtrSlot &s : p->slots) {
+        if (!s.valid) { victim = &s; break; }
+        if (!victim || s.stamp < victim->stamp) victim = &s;
+    }
+    if (victim->valid) {
+        // the last kernels that read this table must have finished
+        e = victim->multi_stream ? hipDeviceSynchronize() : hipEventSynchronize(victim->last_use);
+        if (e != hipSuccess) return hip_fail("waiting for a pointer table to retire", e);
+        victim->valid = false;
+    }
+    if (victim->cap < n) {
+        if (victim->dev) (void)hipFree(victim->dev);
+        if (victim->pinned) (void)hipHostFree(victim->pinned);
+        victim->dev = nullptr; victim->pinned = nullptr; victim->cap = 0;
+        const size_t cap = n < 64 ? 64 : n;
+        e = hipMalloc(&victim->dev, cap * 8);
+        if (e != hipSuccess) return hip_fail("hipMalloc(pointer table)", e);
+        e = hipHostMalloc(reinterpret_cast<void **>(&victim->pinned), cap * 8, hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipFree(victim->dev); victim->dev = nullptr; return hip_fail("hipHostMalloc(pointer table)", e); }
+        victim->cap = cap;
+    }
+    if (!victim->uploaded) {
+        e = hipEventCreateWithFlags(&victim->uploaded, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+        e = hipEventCreateWithFlags(&victim->last_use, hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+    }
+    memcpy(victim->pinned, vals, n * 8);
+    e = hipMemcpyAsync(victim->dev, victim->pinned, n * 8, hipMemcpyHostToDevice, stream);
+    if (e != hipSuccess) return hip_fail("hipMemcpyAsync(pointer table)", e);
+    e = hipEventRecord(victim->uploaded, stream);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    victim->n = n;
+    victim->upload_stream = stream;
+    victim->use_stream = stream;
+    victim->multi_stream = false;
+    victim->valid = true;
+    victim->stamp = ++p->clock;
+    *slot_out = victim;
+    return KT_OK;
+}
+
+static kt_status mark_used(PtrSlot *s, hipStream_t stream)
+{
+    if (s->use_stream != stream) s->multi_stream = true;
+    s->use_stream = stream;
+    hipError_t e = hipEventRecord(s->last_use, stream);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    return KT_OK;
+}
+
+// Resolve the bucket selector into a bucket range and a tile range.
+static kt_status select(const kt_plan *p, int bucket, const char *who, int *b0, int *b1, int64_t *tile0, int64_t *ntiles)
+{
+    const int nb = (int)p->hp.b_elems.size();
+    if (bucket == KT_ALL_BUCKETS) { *b0 = 0; *b1 = nb; }
+    else if (bucket >= 0 && bucket < nb) { *b0 = bucket; *b1 = bucket + 1; }
+    else { kt_set_error("%s: bucket %d outside [0,%d)", who, bucket, nb); return KT_EINVAL; }
+    *tile0 = p->hp.b_tile0[*b0];
+    *ntiles = p->hp.b_tile0[*b1] - *tile0;
+    return KT_OK;
+}
+
+// Shared by pack and unpack: validate, build [tensor ptrs | bucket ptrs], stage.
+static kt_status prepare_tensor_call(kt_plan *p, int bucket, const void *const *tensor_ptrs,
+                                     const void *const *bucket_bufs, const char *who, hipStream_t stream,
+                                     int64_t *tile0, int64_t *ntiles, bool *vector_ok, PtrSlot **slot)
+{
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    int b0, b1;
+    kt_status st = select(p, bucket, who, &b0, &b1, tile0, ntiles);
+    if (st != KT_OK) return st;
+    const KtHostPlan &hp = p->hp;
+    const size_t T = hp.t_numel.size(), nb = hp.b_elems.size();
+    if (*ntiles == 0) return KT_OK;
+    if (!tensor_ptrs || !bucket_bufs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
+    // The whole arrays go into the table (so that per-bucket calls made with
+    // the same arrays share one resident table); only the selected buckets'
+    // entries are validated and dereferenced.
+    std::vector<uint64_t> vals(T + nb, 0);
+    for (size_t t = 0; t < T; ++t) vals[t] = reinterpret_cast<uintptr_t>(tensor_ptrs[t]);
+    for (size_t b = 0; b < nb; ++b) vals[T + b] = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
+    bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
+    for (int b = b0; b < b1; ++b) {
+        const uintptr_t bp = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
+        if (hp.b_elems[b] > 0 && !bp) { kt_set_error("%s: NULL buffer for bucket %d", who, b); return KT_EINVAL; }
+        if (bp & emask) { kt_set_error("%s: bucket %d buffer not aligned to the element size", who, b); return KT_EALIGN; }
+        if (bp & (KT_VEC_BYTES - 1)) vec = false;
+        for (int t = hp.b_first[b]; t < hp.b_first[b] + hp.b_count[b]; ++t) {
+            const uintptr_t tp = reinterpret_cast<uintptr_t>(tensor_ptrs[t]);
+            if (hp.t_numel[t] > 0 && !tp) { kt_set_error("%s: NULL pointer for tensor %d", who, t); return KT_EINVAL; }
+            if (tp & emask) { kt_set_error("%s: tensor %d not aligned to the element size", who, t); return KT_EALIGN; }
+            // a tensor and its bucket must not overlap
+            const uintptr_t tn = (uintptr_t)hp.t_numel[t] * hp.elem_size, bn = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+            if (tn && tp < bp + bn && bp < tp + tn) { kt_set_error("%s: tensor %d overlaps bucket %d", who, t, b); return KT_EINVAL; }
+        }
+    }
+    *vector_ok = vec;
+    st = ensure_device(p);
+    if (st != KT_OK) return st;
+    return stage_pointers(p, vals.data(), vals.size(), stream, slot);
+}
+
+extern "C" kt_status kt_bucket_pack(kt_plan *p, int bucket, const void *const *tensor_ptrs, void *const *bucket_bufs,
+                                    void *stream)
+{
+    if (!p) { kt_set_error("kt_bucket_pack: NULL plan"); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t tile0 = 0, ntiles = 0;
+    bool vec = false;
+    PtrSlot *slot = nullptr;
+    kt_status st = prepare_tensor_call(p, bucket, tensor_ptrs, bucket_bufs, "kt_bucket_pack", s, &tile0, &ntiles, &vec, &slot);
+    if (st != KT_OK || ntiles == 0) return st;
+    const size_t T = p->hp.t_numel.size();
+    const void *const *d_t = static_cast<const void *const *>(slot->dev);
+    void *const *d_b = reinterpret_cast<void *const *>(static_cast<uint64_t *>(slot->dev) + T);
+    int e = kt_launch_pack(p->tb, p->hp.dt, tile0, ntiles, d_t, d_b, vec, stream);
+    if (e != 0) return hip_fail("kt_bucket_pack: launch", (hipError_t)e);
+    return mark_used(slot, s);
+}
+
+extern "C" kt_status kt_bucket_unpack_scale(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
+                                            void *const *tensor_ptrs, void *stream)
+{
+    if (!p) { kt_set_error("kt_bucket_unpack_scale: NULL plan"); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t tile0 = 0, ntiles = 0;
+    bool vec = false;
+    PtrSlot *slot = nullptr;
+    kt_status st = prepare_tensor_call(p, bucket, tensor_ptrs, bucket_bufs, "kt_bucket_unpack_scale", s, &tile0, &ntiles, &vec, &slot);
+    if (st != KT_OK || ntiles == 0) return st;
+    const size_t T = p->hp.t_numel.size();
+    void *const *d_t = static_cast<void *const *>(slot->dev);
+    const void *const *d_b = reinterpret_cast<const void *const *>(static_cast<uint64_t *>(slot->dev) + T);
+    int e = kt_launch_unpack(p->tb, p->hp.dt, tile0, ntiles, d_b, scale, d_t, vec, stream);
+    if (e != 0) return hip_fail("kt_bucket_unpack_scale: launch", (hipError_t)e);
+    return mark_used(slot, s);
+}
+
+extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *const *peer_bufs, int K,
+                                        const float *weights, void *const *out_bufs, void *stream)
+{
+    const char *who = "kt_weighted_reduce";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
+    if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int b0, b1;
+    int64_t tile0, ntiles;
+    kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
+    if (st != KT_OK || ntiles == 0) return st;
+    if (!peer_bufs || !out_bufs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    const KtHostPlan &hp = p->hp;
+    const size_t nb = hp.b_elems.size();
+    const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
+    std::vector<uint64_t> vals(nb * K + nb, 0);
+    for (size_t i = 0; i < nb * K; ++i) vals[i] = reinterpret_cast<uintptr_t>(peer_bufs[i]);
+    for (size_t b = 0; b < nb; ++b) vals[nb * K + b] = reinterpret_cast<uintptr_t>(out_bufs[b]);
+    bool vec = true;
+    for (int b = b0; b < b1; ++b) {
+        const uintptr_t bytes = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+        const uintptr_t op = reinterpret_cast<uintptr_t>(out_bufs[b]);
+        if (bytes && !op) { kt_set_error("%s: NULL output for bucket %d", who, b); return KT_EINVAL; }
+        if (op & emask) { kt_set_error("%s: output %d not aligned to the element size", who, b); return KT_EALIGN; }
+        if (op & (KT_VEC_BYTES - 1)) vec = false;
+        for (int k = 0; k < K; ++k) {
+            const uintptr_t pp = reinterpret_cast<uintptr_t>(peer_bufs[(size_t)b * K + k]);
+            if (bytes && !pp) { kt_set_error("%s: NULL peer %d of bucket %d", who, k, b); return KT_EINVAL; }
+            if (pp & emask) { kt_set_error("%s: peer %d of bucket %d not aligned to the element size", who, k, b); return KT_EALIGN; }
+            if (pp & (KT_VEC_BYTES - 1)) vec = false;
+            // the output may be exactly one of the inputs (in place), never a partial overlap
+            if (bytes && pp != op && pp < op + bytes && op < pp + bytes) {
+                kt_set_error("%s: output of bucket %d partially overlaps peer %d", who, b, k);
+                return KT_EINVAL;
+            }
+        }
+    }
+    KtWeights w;
+    memset(&w, 0, sizeof w);
+    for (int k = 0; k < K; ++k) w.w[k] = weights[k];
+    st = ensure_device(p);
+    if (st != KT_OK) return st;
+    PtrSlot *slot = nullptr;
+    st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
+    if (st != KT_OK) return st;
+    const void *const *d_p = static_cast<const void *const *>(slot->dev);
+    void *const *d_o = reinterpret_cast<void *const *>(static_cast<uint64_t *>(slot->dev) + nb * K);
+    int e = kt_launch_reduce(p->tb, hp.dt, tile0, ntiles, d_p, K, w, d_o, vec, stream);
+    if (e != 0) return hip_fail("kt_weighted_reduce: launch", (hipError_t)e);
+    return mark_used(slot, s);
+}

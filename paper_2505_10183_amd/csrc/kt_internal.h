@@ -1,0 +1,78 @@
+// Internal structures shared by the host plan code, the C ABI and the kernels.
+#ifndef KT_INTERNAL_H
+#define KT_INTERNAL_H
+
+#include <stdint.h>
+#include <vector>
+
+#include "kt.h"
+
+// A tile is a fixed-size slice of one bucket; one workgroup processes one tile.
+#ifndef KT_TILE_BYTES
+#define KT_TILE_BYTES 32768
+#endif
+#define KT_VEC_BYTES 16
+#define KT_TILE_VECS (KT_TILE_BYTES / KT_VEC_BYTES)
+#define KT_BLOCK 256
+// Mixed tiles holding at most this many tensors stage their slice of the
+// tensor table in LDS; larger ones search the table in global memory.
+#define KT_LDS_TENSORS 512
+
+// Per-tile record (device table).  `nt == 0` marks a solid tile: tensor `t0`
+// covers every element of the tile and the tile is a whole number of 16-byte
+// vectors.  Otherwise tensors t0 .. t0+nt-1 are the ones that may own
+// elements of the tile (the rest is padding).
+struct KtTile {
+    int32_t bucket;
+    uint32_t tile_in_bucket;
+    int32_t t0;
+    int32_t nt;
+};
+
+struct KtHostPlan {
+    kt_dtype dt;
+    int elem_size;
+    int64_t cap_bytes;
+    int align_bytes;
+    int64_t tile_elems;
+    // per tensor
+    std::vector<int64_t> t_numel, t_off;
+    std::vector<int32_t> t_bucket;
+    // per bucket
+    std::vector<int64_t> b_elems;
+    std::vector<int32_t> b_first, b_count;
+    std::vector<int64_t> b_tile0;      // first tile of each bucket, nb+1 entries
+    std::vector<KtTile> tiles;
+};
+
+// Builds the layout and the tile table.  Returns KT_OK or an error with `msg` set.
+kt_status kt_build_host_plan(const int64_t *numel, int T, kt_dtype dt,
+                             int64_t cap_bytes, int align_bytes,
+                             KtHostPlan &hp, const char **msg);
+
+// Device-side view of the plan tables plus the per-call pointer tables.
+struct KtDeviceTables {
+    const KtTile *tiles;
+    const int64_t *t_off;
+    const int64_t *t_numel;
+    const int64_t *b_elems;
+};
+
+// Launchers (kt_kernels.hip).  `tile0`/`ntiles` select a contiguous tile range.
+// All return a hipError_t cast to int.
+int kt_launch_pack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                   int64_t ntiles, const void *const *d_tensor_ptrs,
+                   void *const *d_bucket_ptrs, bool vector_ok, void *stream);
+int kt_launch_unpack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                     int64_t ntiles, const void *const *d_bucket_ptrs,
+                     float scale, void *const *d_tensor_ptrs, bool vector_ok,
+                     void *stream);
+struct KtWeights {
+    float w[KT_MAX_PEERS];
+};
+int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                     int64_t ntiles, const void *const *d_peer_ptrs, int K,
+                     const KtWeights &w, void *const *d_out_ptrs,
+                     bool vector_ok, void *stream);
+
+#endif

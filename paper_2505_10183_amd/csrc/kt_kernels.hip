@@ -1,0 +1,560 @@
+// HIP kernels for gfx950: multi-tensor pack / unpack-scale driven by a
+// device-side tile + tensor-offset table, and the K-way weighted reduce.
+//
+// All three are streaming, zero-reuse, HBM-bound kernels.  One workgroup of
+// 256 lanes (4 wavefronts) processes one tile of KT_TILE_BYTES of a bucket;
+// each lane moves 16-byte vectors, several in flight before the first use.
+// Nothing here is a contraction, so no MFMA.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kt_internal.h"
+
+#ifndef KT_NT_LOAD
+#define KT_NT_LOAD 1
+#endif
+#ifndef KT_NT_STORE
+#define KT_NT_STORE 1
+#endif
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int VE = 4; };
+template <> struct Elem<uint16_t> { static constexpr int VE = 8; };
+
+// Every data pointer reaches the kernels through a pointer table in memory,
+// so the compiler cannot tell that it addresses global memory and would emit
+// flat loads/stores.  The data is always in global memory: say so.
+#define KT_GLOBAL __attribute__((address_space(1)))
+
+__device__ __forceinline__ u32x4 ld_vec(const void *p)
+{
+    const KT_GLOBAL u32x4 *g = (const KT_GLOBAL u32x4 *)p;
+#if KT_NT_LOAD
+    return __builtin_nontemporal_load(g);
+#else
+    return *g;
+#endif
+}
+
+__device__ __forceinline__ void st_vec(void *p, u32x4 v)
+{
+    KT_GLOBAL u32x4 *g = (KT_GLOBAL u32x4 *)p;
+#if KT_NT_STORE
+    __builtin_nontemporal_store(v, g);
+#else
+    *g = v;
+#endif
+}
+
+template <typename T> __device__ __forceinline__ T ld_elem(const T *p) { return *(const KT_GLOBAL T *)p; }
+template <typename T> __device__ __forceinline__ void st_elem(T *p, T v) { *(KT_GLOBAL T *)p = v; }
+
+// bf16 <-> binary32.  Widening is exact (the bits become the upper half);
+// narrowing is round-to-nearest-even on the bit pattern, NaN stays quiet NaN.
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// scale * x for one element of either storage type
+__device__ __forceinline__ float scale_elem(float x, float s) { return __fmul_rn(s, x); }
+__device__ __forceinline__ uint16_t scale_elem(uint16_t x, float s)
+{
+    return (uint16_t)f32_to_bf16(__fmul_rn(s, __uint_as_float((uint32_t)x << 16)));
+}
+
+template <typename T> __device__ __forceinline__ u32x4 scale_vec(u32x4 v, float s);
+template <> __device__ __forceinline__ u32x4 scale_vec<float>(u32x4 v, float s)
+{
+    u32x4 r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) r[c] = __float_as_uint(__fmul_rn(s, __uint_as_float(v[c])));
+    return r;
+}
+template <> __device__ __forceinline__ u32x4 scale_vec<uint16_t>(u32x4 v, float s)
+{
+    u32x4 r;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        uint32_t lo = f32_to_bf16(__fmul_rn(s, bf16_lo(v[c])));
+        uint32_t hi = f32_to_bf16(__fmul_rn(s, bf16_hi(v[c])));
+        r[c] = lo | (hi << 16);
+    }
+    return r;
+}
+
+// ---- tensor-table views for mixed tiles ---------------------------------
+// A view exposes, for local index i in [0, nt): the tensor's element offset in
+// the bucket, its element count and its base address.
+
+struct TableView {
+    const int64_t *off;
+    const int64_t *numel;
+    const uintptr_t *ptr;
+};
+
+// last i in [0, nt) with off[i] <= e, or -1
+__device__ __forceinline__ int find_owner(const TableView &tv, int nt, int64_t e)
+{
+    int lo = 0, hi = nt;
+    while (lo < hi) {
+        int mid = (lo + hi) >> 1;
+        if (tv.off[mid] <= e) lo = mid + 1; else hi = mid;
+    }
+    return lo - 1;
+}
+
+struct TileGeom {
+    int bucket;
+    int64_t start;   // first element of the tile inside the bucket
+    int64_t end;     // one past the last element (clipped to the bucket length)
+};
+
+__device__ __forceinline__ TileGeom tile_geom(const KtTile &tl, const int64_t *b_elems, int64_t tile_elems)
+{
+    TileGeom g;
+    g.bucket = tl.bucket;
+    g.start = (int64_t)tl.tile_in_bucket * tile_elems;
+    int64_t n = b_elems[tl.bucket];
+    g.end = g.start + tile_elems < n ? g.start + tile_elems : n;
+    return g;
+}
+
+// Stage the tile's slice of the tensor table in LDS when it fits, so that the
+// per-vector owner search runs on LDS instead of global memory.
+struct LdsTable {
+    int64_t off[KT_LDS_TENSORS];
+    int64_t numel[KT_LDS_TENSORS];
+    uintptr_t ptr[KT_LDS_TENSORS];
+};
+
+__device__ __forceinline__ TableView stage_table(LdsTable &lds, const KtDeviceTables &tb,
+                                                 const void *const *tensor_ptrs, int t0, int nt)
+{
+    TableView tv;
+    if (nt <= KT_LDS_TENSORS) {
+        for (int i = threadIdx.x; i < nt; i += KT_BLOCK) {
+            lds.off[i] = tb.t_off[t0 + i];
+            lds.numel[i] = tb.t_numel[t0 + i];
+            lds.ptr[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[t0 + i]);
+        }
+        __syncthreads();
+        tv.off = lds.off; tv.numel = lds.numel; tv.ptr = lds.ptr;
+    } else {
+        tv.off = tb.t_off + t0; tv.numel = tb.t_numel + t0;
+        tv.ptr = reinterpret_cast<const uintptr_t *>(tensor_ptrs) + t0;
+    }
+    return tv;
+}
+
+// ---- pack ----------------------------------------------------------------
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(KT_BLOCK) void kt_pack_kernel(KtDeviceTables tb, int64_t tile0,
+                                                           const void *const *tensor_ptrs,
+                                                           void *const *bucket_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    __shared__ LdsTable lds;
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    T *dst = reinterpret_cast<T *>(bucket_ptrs[g.bucket]);
+    const int tid = threadIdx.x;
+
+    if (VEC && tl.nt == 0) {
+        // Solid tile: one tensor owns everything; straight 16-byte copy when
+        // the source address is 16-byte aligned.
+        const T *src = reinterpret_cast<const T *>(tensor_ptrs[tl.t0]) + (g.start - tb.t_off[tl.t0]);
+        if ((reinterpret_cast<uintptr_t>(src) & 15u) == 0) {
+            const u32x4 *s4 = reinterpret_cast<const u32x4 *>(src);
+            u32x4 *d4 = reinterpret_cast<u32x4 *>(dst + g.start);
+            const int nvec = (int)((g.end - g.start) / VE);
+            if (nvec == KT_TILE_VECS) {
+                u32x4 r[VPT];
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) r[j] = ld_vec(s4 + j * KT_BLOCK + tid);
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) st_vec(d4 + j * KT_BLOCK + tid, r[j]);
+            } else {
+#pragma unroll 1
+                for (int v = tid; v < nvec; v += KT_BLOCK) st_vec(d4 + v, ld_vec(s4 + v));
+            }
+            return;
+        }
+    }
+
+    const int nt = tl.nt == 0 ? 1 : tl.nt;
+    const TableView tv = stage_table(lds, tb, tensor_ptrs, tl.t0, nt);
+
+    if (VEC) {
+        const int64_t b_n = tb.b_elems[g.bucket];
+        const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+        for (int v = tid; v < nvec; v += KT_BLOCK) {
+            const int64_t e0 = g.start + (int64_t)v * VE;
+            int i = find_owner(tv, nt, e0);
+            bool whole = false;
+            u32x4 val;
+            if (i >= 0) {
+                const int64_t r = e0 - tv.off[i];
+                if (r + VE <= tv.numel[i]) {
+                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                    if ((p & 15u) == 0) {
+                        val = ld_vec(reinterpret_cast<const void *>(p));
+                        whole = true;
+                    }
+                }
+            }
+            if (whole && e0 + VE <= b_n) {
+                st_vec(dst + e0, val);
+                continue;
+            }
+            // element-wise: tensor tails, padding, misaligned sources, and the
+            // last partial vector of a densely packed bucket
+#pragma unroll 1
+            for (int q = 0; q < VE; ++q) {
+                const int64_t e = e0 + q;
+                if (e >= b_n) break;
+                while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+                T x = 0;
+                if (i >= 0 && e - tv.off[i] < tv.numel[i])
+                    x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
+                st_elem(dst + e, x);
+            }
+        }
+    } else {
+        // any alignment: one element per lane per step, coalesced
+        for (int64_t e = g.start + tid; e < g.end; e += KT_BLOCK) {
+            const int i = find_owner(tv, nt, e);
+            T x = 0;
+            if (i >= 0 && e - tv.off[i] < tv.numel[i])
+                x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
+            st_elem(dst + e, x);
+        }
+    }
+}
+
+// ---- unpack with scale ----------------------------------------------------
+
+template <typename T, bool VEC>
+__global__ __launch_bounds__(KT_BLOCK) void kt_unpack_kernel(KtDeviceTables tb, int64_t tile0,
+                                                             const void *const *bucket_ptrs, float scale,
+                                                             void *const *tensor_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    __shared__ LdsTable lds;
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const T *src = reinterpret_cast<const T *>(bucket_ptrs[g.bucket]);
+    const int tid = threadIdx.x;
+
+    if (VEC && tl.nt == 0) {
+        T *dst = reinterpret_cast<T *>(tensor_ptrs[tl.t0]) + (g.start - tb.t_off[tl.t0]);
+        if ((reinterpret_cast<uintptr_t>(dst) & 15u) == 0) {
+            const u32x4 *s4 = reinterpret_cast<const u32x4 *>(src + g.start);
+            u32x4 *d4 = reinterpret_cast<u32x4 *>(dst);
+            const int nvec = (int)((g.end - g.start) / VE);
+            if (nvec == KT_TILE_VECS) {
+                u32x4 r[VPT];
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) r[j] = ld_vec(s4 + j * KT_BLOCK + tid);
+#pragma unroll
+                for (int j = 0; j < VPT; ++j) st_vec(d4 + j * KT_BLOCK + tid, scale_vec<T>(r[j], scale));
+            } else {
+#pragma unroll 1
+                for (int v = tid; v < nvec; v += KT_BLOCK) st_vec(d4 + v, scale_vec<T>(ld_vec(s4 + v), scale));
+            }
+            return;
+        }
+    }
+
+    const int nt = tl.nt == 0 ? 1 : tl.nt;
+    const TableView tv = stage_table(lds, tb, reinterpret_cast<const void *const *>(tensor_ptrs), tl.t0, nt);
+
+    if (VEC) {
+        const int64_t b_n = tb.b_elems[g.bucket];
+        const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+        for (int v = tid; v < nvec; v += KT_BLOCK) {
+            const int64_t e0 = g.start + (int64_t)v * VE;
+            int i = find_owner(tv, nt, e0);
+            const bool in_bucket = e0 + VE <= b_n;
+            if (in_bucket && i >= 0) {
+                const int64_t r = e0 - tv.off[i];
+                if (r + VE <= tv.numel[i]) {
+                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                    if ((p & 15u) == 0) {
+                        st_vec(reinterpret_cast<void *>(p), scale_vec<T>(ld_vec(src + e0), scale));
+                        continue;
+                    }
+                }
+            }
+#pragma unroll 1
+            for (int q = 0; q < VE; ++q) {
+                const int64_t e = e0 + q;
+                if (e >= b_n) break;
+                while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+                if (i >= 0 && e - tv.off[i] < tv.numel[i])
+                    st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
+            }
+        }
+    } else {
+        for (int64_t e = g.start + tid; e < g.end; e += KT_BLOCK) {
+            const int i = find_owner(tv, nt, e);
+            if (i >= 0 && e - tv.off[i] < tv.numel[i])
+                st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
+        }
+    }
+}
+
+// ---- K-way weighted reduce ------------------------------------------------
+// Per element: acc = w0*x0 (rounded), then acc = fma(wk, xk, acc), ascending k.
+
+template <typename T> struct Acc;
+template <> struct Acc<float> {
+    float a[4];
+    __device__ __forceinline__ void first(u32x4 x, float w)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[c] = __fmul_rn(w, __uint_as_float(x[c]));
+    }
+    __device__ __forceinline__ void add(u32x4 x, float w)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a[c] = __fmaf_rn(w, __uint_as_float(x[c]), a[c]);
+    }
+    __device__ __forceinline__ u32x4 finish() const
+    {
+        u32x4 r;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[c] = __float_as_uint(a[c]);
+        return r;
+    }
+};
+template <> struct Acc<uint16_t> {
+    float a[8];
+    __device__ __forceinline__ void first(u32x4 x, float w)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[2 * c] = __fmul_rn(w, bf16_lo(x[c]));
+            a[2 * c + 1] = __fmul_rn(w, bf16_hi(x[c]));
+        }
+    }
+    __device__ __forceinline__ void add(u32x4 x, float w)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            a[2 * c] = __fmaf_rn(w, bf16_lo(x[c]), a[2 * c]);
+            a[2 * c + 1] = __fmaf_rn(w, bf16_hi(x[c]), a[2 * c + 1]);
+        }
+    }
+    __device__ __forceinline__ u32x4 finish() const
+    {
+        u32x4 r;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) r[c] = f32_to_bf16(a[2 * c]) | (f32_to_bf16(a[2 * c + 1]) << 16);
+        return r;
+    }
+};
+
+__device__ __forceinline__ float widen(float x) { return x; }
+__device__ __forceinline__ float widen(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+template <typename T> __device__ __forceinline__ T narrow(float a);
+template <> __device__ __forceinline__ float narrow<float>(float a) { return a; }
+template <> __device__ __forceinline__ uint16_t narrow<uint16_t>(float a) { return (uint16_t)f32_to_bf16(a); }
+
+// Vectors in flight per lane before the first use (K loads each).
+template <int K> struct Unroll { static constexpr int U = K <= 2 ? 8 : (K <= 4 ? 4 : 2); };
+
+template <typename T, int K>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
+                                                             const void *const *peer_ptrs, KtWeights wts,
+                                                             void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    constexpr int U = Unroll<K>::U;
+    static_assert(VPT % U == 0, "unroll must divide vectors per lane");
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const int tid = threadIdx.x;
+
+    const T *x[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) x[k] = reinterpret_cast<const T *>(peer_ptrs[(int64_t)g.bucket * K + k]) + g.start;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
+    float w[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) w[k] = wts.w[k];
+
+    const int64_t n = g.end - g.start;
+    const int nvec = (int)(n / VE);
+
+    if (nvec == KT_TILE_VECS) {
+#pragma unroll 1
+        for (int j = 0; j < VPT; j += U) {
+            u32x4 r[U][K];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int k = 0; k < K; ++k)
+                    r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + (j + u) * KT_BLOCK + tid);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                Acc<T> acc;
+                acc.first(r[u][0], w[0]);
+#pragma unroll
+                for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
+                st_vec(reinterpret_cast<u32x4 *>(out) + (j + u) * KT_BLOCK + tid, acc.finish());
+            }
+        }
+    } else {
+        for (int v = tid; v < nvec; v += KT_BLOCK) {
+            u32x4 r[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k) r[k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + v);
+            Acc<T> acc;
+            acc.first(r[0], w[0]);
+#pragma unroll
+            for (int k = 1; k < K; ++k) acc.add(r[k], w[k]);
+            st_vec(reinterpret_cast<u32x4 *>(out) + v, acc.finish());
+        }
+        // tail of a densely packed bucket (fewer than VE elements)
+        const int64_t e = (int64_t)nvec * VE + tid;
+        if (e < n) {
+            float a = __fmul_rn(w[0], widen(ld_elem(x[0] + e)));
+#pragma unroll
+            for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k] + e)), a);
+            st_elem(out + e, narrow<T>(a));
+        }
+    }
+}
+
+// Any K (weights in the kernel argument block), 16-byte vectors.
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_anyk_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                  const void *const *peer_ptrs, int K,
+                                                                  KtWeights wts, void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const int tid = threadIdx.x;
+    const void *const *pp = peer_ptrs + (int64_t)g.bucket * K;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
+    const int64_t n = g.end - g.start;
+    const int nvec = (int)(n / VE);
+    for (int v = tid; v < nvec; v += KT_BLOCK) {
+        Acc<T> acc;
+        acc.first(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[0]) + g.start) + v), wts.w[0]);
+#pragma unroll 4
+        for (int k = 1; k < K; ++k)
+            acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k]) + g.start) + v), wts.w[k]);
+        st_vec(reinterpret_cast<u32x4 *>(out) + v, acc.finish());
+    }
+    const int64_t e = (int64_t)nvec * VE + tid;
+    if (e < n) {
+        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + g.start + e)));
+        for (int k = 1; k < K; ++k)
+            a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + g.start + e)), a);
+        st_elem(out + e, narrow<T>(a));
+    }
+}
+
+// Any K, any alignment: one element per lane per step.
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_elem_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                  const void *const *peer_ptrs, int K,
+                                                                  KtWeights wts, void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const void *const *pp = peer_ptrs + (int64_t)g.bucket * K;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]);
+    for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
+        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + e)));
+        for (int k = 1; k < K; ++k) a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + e)), a);
+        st_elem(out + e, narrow<T>(a));
+    }
+}
+
+template <typename T>
+hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntiles, const void *const *peers,
+                           int K, const KtWeights &w, void *const *outs, bool vector_ok, hipStream_t s)
+{
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (!vector_ok) {
+        kt_reduce_elem_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs);
+        return hipGetLastError();
+    }
+    switch (K) {
+#define KT_CASE(KK) \
+    case KK: kt_reduce_kernel<T, KK><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
+        KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
+#undef KT_CASE
+    default: kt_reduce_anyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int kt_launch_pack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                   const void *const *d_tensor_ptrs, void *const *d_bucket_ptrs, bool vector_ok, void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (dt == KT_F32) {
+        if (vector_ok) kt_pack_kernel<float, true><<<grid, block, 0, s>>>(tb, tile0, d_tensor_ptrs, d_bucket_ptrs);
+        else kt_pack_kernel<float, false><<<grid, block, 0, s>>>(tb, tile0, d_tensor_ptrs, d_bucket_ptrs);
+    } else {
+        if (vector_ok) kt_pack_kernel<uint16_t, true><<<grid, block, 0, s>>>(tb, tile0, d_tensor_ptrs, d_bucket_ptrs);
+        else kt_pack_kernel<uint16_t, false><<<grid, block, 0, s>>>(tb, tile0, d_tensor_ptrs, d_bucket_ptrs);
+    }
+    return (int)hipGetLastError();
+}
+
+int kt_launch_unpack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                     const void *const *d_bucket_ptrs, float scale, void *const *d_tensor_ptrs, bool vector_ok,
+                     void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (dt == KT_F32) {
+        if (vector_ok) kt_unpack_kernel<float, true><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, scale, d_tensor_ptrs);
+        else kt_unpack_kernel<float, false><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, scale, d_tensor_ptrs);
+    } else {
+        if (vector_ok) kt_unpack_kernel<uint16_t, true><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, scale, d_tensor_ptrs);
+        else kt_unpack_kernel<uint16_t, false><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, scale, d_tensor_ptrs);
+    }
+    return (int)hipGetLastError();
+}
+
+int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                     const void *const *d_peer_ptrs, int K, const KtWeights &w, void *const *d_out_ptrs,
+                     bool vector_ok, void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dt == KT_F32) return (int)launch_reduce_t<float>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
+    return (int)launch_reduce_t<uint16_t>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
+}

@@ -1,0 +1,394 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU checker
+on the same seeded inputs.  Integer / index / copy work must be bit-exact;
+the fp32 reduce must satisfy |gpu - checker_D| <= 1e-6 * max|g| + 1e-9 (max
+over all K peer inputs of the bucket) and bf16 results must lie within one
+bf16 ulp of checker mode D; against checker mode S (same binary32 steps) the
+results are expected bit-identical."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_10183_amd as kt
+from paper_2505_10183_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------- helpers ----
+
+def tdtype(dtype):
+    return torch.float32 if dtype == "f32" else torch.bfloat16
+
+
+def host(t):
+    return wl.to_host_array(t)
+
+
+def raw(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def bf16_ordered(bits):
+    """Map bf16 bit patterns to integers whose difference counts ulps."""
+    b = bits.astype(np.int32)
+    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
+
+
+def assert_close(got, want_D, dtype, gmax, what=""):
+    if dtype == "f32":
+        tol = 1e-6 * gmax + 1e-9
+        err = np.abs(got.astype(np.float64) - want_D.astype(np.float64))
+        bad = ~(err <= tol)
+        assert not bad.any(), "%s: max err %g > tol %g at %d" % (what, np.nanmax(err), tol, int(np.argmax(bad)))
+    else:
+        d = np.abs(bf16_ordered(got) - bf16_ordered(want_D))
+        assert d.max() <= 1, "%s: %d bf16 ulps at %d" % (what, d.max(), int(np.argmax(d)))
+
+
+def alloc_buckets(plan, dtype, fill=None):
+    bufs = []
+    for n in plan.bucket_elems():
+        t = torch.empty(n, dtype=tdtype(dtype), device=DEV)
+        if fill is not None:
+            t.view(torch.int16 if dtype == "bf16" else torch.int32).fill_(fill)
+        bufs.append(t)
+    return bufs
+
+
+def layout_for(w, align):
+    return oracle.assign_buckets(w.numels, w.elem_size, w.bucket_cap_bytes, align)
+
+
+def tagged_tensors(w, seed=0):
+    """Raw bit-pattern tags, including NaN payloads and denormals (pack must
+    copy bits, not values)."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for n in w.numels:
+        if w.dtype == "f32":
+            bits = rng.integers(0, 2 ** 32, size=n, dtype=np.uint64).astype(np.uint32)
+            t = torch.from_numpy(bits.view(np.int32)).to(DEV).view(torch.float32)
+        else:
+            bits = rng.integers(0, 2 ** 16, size=n, dtype=np.uint64).astype(np.uint16)
+            t = torch.from_numpy(bits.view(np.int16)).to(DEV).view(torch.bfloat16)
+        out.append(t)
+    return out
+
+
+# ---------------------------------------------------------------- pack ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("align", [16, 0, 256])
+@pytest.mark.parametrize("batched", [True, False])
+def test_pack_bit_exact(dtype, align, batched):
+    w = wl.ragged_workload(dtype=dtype, seed=21)
+    align = align or w.elem_size
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, align)
+    L = layout_for(w, align)
+    tensors = tagged_tensors(w, seed=3)
+    bufs = alloc_buckets(plan, dtype, fill=0x5A5A if dtype == "bf16" else 0x5A5A5A5A)
+    if batched:
+        plan.kt_bucket_pack(kt.binding.KT_ALL_BUCKETS, tensors, bufs)
+    else:
+        for b in range(plan.num_buckets):
+            plan.kt_bucket_pack(b, tensors, bufs)
+    torch.cuda.synchronize()
+    want = oracle.pack(L, [host(t) for t in tensors], dtype)
+    for b in range(plan.num_buckets):
+        assert raw(host(bufs[b])).tobytes() == raw(want[b]).tobytes(), "bucket %d" % b
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_pack_unpack_misaligned_pointers(dtype):
+    """Tensor and bucket addresses that are only element-aligned."""
+    w = wl.ragged_workload(dtype=dtype, seed=22, n_tensors=30)
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+    L = layout_for(w, 16)
+    base = tagged_tensors(w, seed=4)
+    # odd tensors live one element into a larger allocation
+    tensors = []
+    for i, t in enumerate(base):
+        if i % 2:
+            big = torch.zeros(t.numel() + 3, dtype=t.dtype, device=DEV)
+            big[1:1 + t.numel()] = t
+            tensors.append(big[1:1 + t.numel()])
+        else:
+            tensors.append(t)
+    want = oracle.pack(L, [host(t) for t in tensors], dtype)
+    for shift in (0, 1):          # aligned buckets, then buckets off by one element
+        store = [torch.zeros(n + 8, dtype=tdtype(dtype), device=DEV) for n in plan.bucket_elems()]
+        bufs = [s[shift:shift + n] for s, n in zip(store, plan.bucket_elems())]
+        plan.kt_bucket_pack(-1, tensors, bufs)
+        torch.cuda.synchronize()
+        for b in range(plan.num_buckets):
+            assert raw(host(bufs[b])).tobytes() == raw(want[b]).tobytes(), (shift, b)
+            assert int(store[b][shift + bufs[b].numel():].view(torch.int16).abs().sum()) == 0
+        # unpack with scale 1 into canary-guarded tensors (finite values only)
+        fin = wl.gradient_set(w, 0, DEV)
+        plan.kt_bucket_pack(-1, fin, bufs)
+        outs_store = [torch.full((t.numel() + 6,), 7.0, dtype=t.dtype, device=DEV) for t in fin]
+        outs = [s[(3 if i % 2 else 0):(3 if i % 2 else 0) + t.numel()] for i, (s, t) in enumerate(zip(outs_store, fin))]
+        plan.kt_bucket_unpack_scale(-1, bufs, 1.0, outs)
+        torch.cuda.synchronize()
+        for i, (o, t, s) in enumerate(zip(outs, fin, outs_store)):
+            assert torch.equal(o, t), i
+            lo = 3 if i % 2 else 0
+            assert bool((s[:lo] == 7.0).all()) and bool((s[lo + t.numel():] == 7.0).all()), i
+
+
+def test_pack_tiny_tensors_only():
+    """Every tensor is 1..7 elements: all tiles are mixed, most vectors partial."""
+    numels = [1, 3, 5, 7, 2, 1, 1, 6, 4, 1] * 120
+    for dtype, align in (("f32", 16), ("bf16", 16), ("f32", 4), ("bf16", 2)):
+        es = 4 if dtype == "f32" else 2
+        plan = kt.Plan(numels, dtype, 0, align)
+        L = oracle.assign_buckets(numels, es, 0, align)
+        w = wl.Workload("tiny", dtype, tuple((n,) for n in numels), (1.0,), 1, 0, 1.0, 5)
+        tensors = tagged_tensors(w, seed=6)
+        bufs = alloc_buckets(plan, dtype, fill=0x1111)
+        plan.kt_bucket_pack(-1, tensors, bufs)
+        torch.cuda.synchronize()
+        want = oracle.pack(L, [host(t) for t in tensors], dtype)
+        assert raw(host(bufs[0])).tobytes() == raw(want[0]).tobytes(), (dtype, align)
+
+
+def test_pack_more_tensors_than_lds_table():
+    """A 32 KiB tile overlapped by more than 512 tensors takes the global-table search."""
+    numels = [4] * 3000 + [50000] + [3] * 100
+    plan = kt.Plan(numels, "f32", 0, 16)
+    L = oracle.assign_buckets(numels, 4, 0, 16)
+    w = wl.Workload("many", "f32", tuple((n,) for n in numels), (1.0,), 1, 0, 1.0, 5)
+    tensors = tagged_tensors(w, seed=8)
+    bufs = alloc_buckets(plan, "f32", fill=0x2222)
+    plan.kt_bucket_pack(-1, tensors, bufs)
+    torch.cuda.synchronize()
+    want = oracle.pack(L, [host(t) for t in tensors], "f32")
+    assert raw(host(bufs[0])).tobytes() == raw(want[0]).tobytes()
+    fin = wl.gradient_set(w, 0, DEV)
+    plan.kt_bucket_pack(-1, fin, bufs)
+    outs = [torch.zeros_like(t) for t in fin]
+    plan.kt_bucket_unpack_scale(-1, bufs, 0.5, outs)
+    torch.cuda.synchronize()
+    for o, t in zip(outs, fin):
+        assert torch.equal(o, t * 0.5)
+
+
+# -------------------------------------------------------------- unpack ----
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("align", [16, 0])
+@pytest.mark.parametrize("scale", [1.0, 0.5, 0.37])
+def test_unpack_scale(dtype, align, scale):
+    w = wl.ragged_workload(dtype=dtype, seed=23)
+    align = align or w.elem_size
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, align)
+    L = layout_for(w, align)
+    nb = plan.num_buckets
+    # bucket contents: seeded Gaussians, including the padding positions
+    bufs = [wl.flat_normal(n, dtype, 1e-3, 100 + b, DEV) for b, n in enumerate(plan.bucket_elems())]
+    stores = [torch.full((n + 16,), 3.0, dtype=tdtype(dtype), device=DEV) for n in w.numels]
+    outs = [s[8:8 + n] for s, n in zip(stores, w.numels)]
+    for b in range(nb):
+        plan.kt_bucket_unpack_scale(b, bufs, scale, outs)
+    torch.cuda.synchronize()
+    hb = [host(b) for b in bufs]
+    wantD = oracle.unpack_scale(L, hb, w.numels, scale, dtype, "D")
+    wantS = oracle.unpack_scale(L, hb, w.numels, scale, dtype, "S")
+    for t in range(len(w.numels)):
+        got = host(outs[t])
+        assert raw(got).tobytes() == raw(wantS[t]).tobytes(), t
+        if dtype == "f32":
+            assert raw(got).tobytes() == raw(wantD[t]).tobytes(), t
+        else:
+            assert_close(got, wantD[t], dtype, 0.0, "tensor %d" % t)
+        s = stores[t]
+        assert bool((s[:8] == 3.0).all()) and bool((s[8 + w.numels[t]:] == 3.0).all()), t
+
+
+# -------------------------------------------------------------- reduce ----
+
+def run_reduce(plan, peers, weights, outs=None, bucket=-1):
+    nb, K = plan.num_buckets, len(peers)
+    flat = [peers[k][b] for b in range(nb) for k in range(K)]
+    if outs is None:
+        outs = [torch.empty_like(peers[0][b]) for b in range(nb)]
+    plan.kt_weighted_reduce(bucket, flat, K, list(weights), outs)
+    torch.cuda.synchronize()
+    return outs
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8, 9, 16])
+def test_reduce_vs_checker(dtype, K):
+    w = wl.ragged_workload(dtype=dtype, K=K, seed=30 + K)
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+    shares, weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
+    assert shares == oracle.plan_shares(w.throughputs, w.global_batch)
+    wts = oracle.share_weights(shares, w.global_batch)
+    assert np.array(weights, dtype=np.float32).tobytes() == wts.tobytes()
+    peers = [[wl.flat_normal(n, dtype, w.sigma, 1000 * k + b, DEV) for b, n in enumerate(plan.bucket_elems())]
+             for k in range(K)]
+    outs = run_reduce(plan, peers, weights)
+    for b in range(plan.num_buckets):
+        hp = [host(peers[k][b]) for k in range(K)]
+        got = host(outs[b])
+        wantD = oracle.weighted_reduce(hp, wts, dtype, "D")
+        wantS = oracle.weighted_reduce(hp, wts, dtype, "S")
+        if dtype == "f32":
+            gmax = max(float(np.abs(x).max()) for x in hp)
+        else:
+            gmax = 0.0
+        assert_close(got, wantD, dtype, gmax, "bucket %d" % b)
+        assert raw(got).tobytes() == raw(wantS).tobytes(), "strict mode, bucket %d" % b
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_reduce_identical_peers_and_integers(dtype):
+    name = "vit_b16" if dtype == "f32" else "decoder_1p3b"
+    cfg = wl.WORKLOADS[name]
+    K = cfg.K
+    numels = [70001, 5, 12345]
+    plan = kt.Plan(numels, dtype, 0, 16)
+    shares, weights = kt.kt_plan_shares(cfg.throughputs, cfg.global_batch)
+    n = plan.bucket_elems()[0]
+    x = wl.flat_normal(n, dtype, cfg.sigma, 77, DEV)
+    outs = run_reduce(plan, [[x]] * K, weights)
+    if dtype == "bf16":
+        # 8-bit significands times <= 12-bit shares: no product or sum rounds
+        assert torch.equal(outs[0], x)
+    else:
+        gmax = float(x.abs().max())
+        assert_close(host(outs[0]), host(x), dtype, gmax, "identical peers")
+    # integer-valued gradients, all-ones weights: exact integer sums
+    ints = [torch.randint(-64, 65, (n,), device=DEV, generator=torch.Generator(DEV).manual_seed(k)).to(tdtype(dtype))
+            for k in range(K)]
+    outs = run_reduce(plan, [[t] for t in ints], [1.0] * K)
+    ref = sum(t.to(torch.int64) for t in ints)
+    assert torch.equal(outs[0].to(torch.int64), ref)
+    if dtype == "f32":
+        # w = b_k / B with B a power of two: exactly (sum_k b_k x_k) / B
+        outs = run_reduce(plan, [[t] for t in ints], weights)
+        num = sum(int(s) * t.to(torch.int64) for s, t in zip(shares, ints))
+        assert torch.equal((outs[0].double() * cfg.global_batch).to(torch.int64), num)
+    # one-hot weights select a peer bit for bit
+    oh = [0.0] * K
+    oh[K - 2] = 1.0
+    outs = run_reduce(plan, [[t] for t in ints], oh)
+    assert torch.equal(outs[0], ints[K - 2])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_reduce_in_place_and_misaligned_and_dense(dtype):
+    K = 4
+    es = 4 if dtype == "f32" else 2
+    numels = [33001, 7, 1, 40003]
+    wts = oracle.share_weights([91, 73, 46, 46], 256)
+    for align in (16, es):
+        plan = kt.Plan(numels, dtype, 0, align)
+        n = plan.bucket_elems()[0]
+        if align == es:
+            assert n % (16 // es) != 0          # ragged tail shorter than a vector
+        for shift in (0, 1):                    # 16-byte aligned, then element-aligned only
+            store = [wl.flat_normal(n + 8, dtype, 1e-3, 50 + k, DEV) for k in range(K)]
+            peers = [[s[shift:shift + n]] for s in store]
+            hp = [host(p[0]) for p in peers]
+            wantS = oracle.weighted_reduce(hp, wts, dtype, "S")
+            tails = [s[shift + n:].clone() for s in store]
+            # in place: the output is peer 2
+            run_reduce(plan, peers, list(wts), outs=[peers[2][0]])
+            assert raw(host(peers[2][0])).tobytes() == raw(wantS).tobytes(), (align, shift)
+            for s, tl in zip(store, tails):
+                assert torch.equal(s[shift + n:], tl)
+            for k in (0, 1, 3):
+                assert raw(host(peers[k][0])).tobytes() == raw(hp[k]).tobytes()
+
+
+def test_reduce_single_bucket_selection():
+    w = wl.ragged_workload(dtype="f32", K=3, seed=41)
+    plan = kt.Plan(w.numels, "f32", w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    wts = [0.5, 0.25, 0.25]
+    peers = [[wl.flat_normal(n, "f32", 1e-3, 10 * k + b, DEV) for b, n in enumerate(plan.bucket_elems())] for k in range(3)]
+    outs = [torch.full((n,), 9.0, device=DEV) for n in plan.bucket_elems()]
+    run_reduce(plan, peers, wts, outs=outs, bucket=nb - 2)
+    for b in range(nb):
+        if b == nb - 2:
+            want = oracle.weighted_reduce([host(peers[k][b]) for k in range(3)], np.array(wts, np.float32), "f32", "S")
+            assert raw(host(outs[b])).tobytes() == raw(want).tobytes()
+        else:
+            assert bool((outs[b] == 9.0).all())
+
+
+def test_special_values():
+    """NaN / Inf / zero weights follow IEEE: 0 * Inf = NaN propagates."""
+    plan = kt.Plan([16], "f32", 0, 16)
+    a = torch.tensor([1.0, float("inf"), float("-inf"), float("nan"), 0.0, -0.0, 1e-45, 3e38] * 2, device=DEV)
+    b = torch.tensor([2.0, 1.0, float("inf"), 1.0, -0.0, -0.0, 1e-45, 3e38] * 2, device=DEV)
+    for wts in ([0.5, 0.5], [0.0, 1.0], [1.0, 1.0]):
+        outs = run_reduce(plan, [[a], [b]], wts)
+        want = oracle.weighted_reduce([host(a), host(b)], np.array(wts, np.float32), "f32", "S")
+        got = host(outs[0])
+        same = (raw(got) == raw(want)) | (np.isnan(got) & np.isnan(want))
+        assert same.all(), wts
+    planb = kt.Plan([16], "bf16", 0, 16)
+    ab, bb = a.to(torch.bfloat16), b.to(torch.bfloat16)
+    outs = run_reduce(planb, [[ab], [bb]], [0.5, 0.5])
+    want = oracle.weighted_reduce([host(ab), host(bb)], np.array([0.5, 0.5], np.float32), "bf16", "S")
+    got = host(outs[0])
+    gotf, wantf = oracle.bf16_to_f32_array(got), oracle.bf16_to_f32_array(want)
+    assert ((got == want) | (np.isnan(gotf) & np.isnan(wantf))).all()
+
+
+# ---------------------------------------------------------- end to end ----
+
+def full_step_check(name, align=16, scale=1.0):
+    """pack (K times) -> reduce -> unpack on a whole workload, every element
+    against the checker, bucketed and un-bucketed."""
+    w = wl.WORKLOADS[name]
+    K, dtype = w.K, w.dtype
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, align)
+    L = layout_for(w, align)
+    shares, weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
+    assert shares == oracle.plan_shares(w.throughputs, w.global_batch)
+    wts = oracle.share_weights(shares, w.global_batch)
+    grads = [wl.gradient_set(w, k, DEV) for k in range(K)]
+    peers = [alloc_buckets(plan, dtype, fill=0x7F7F if dtype == "bf16" else 0x7F7F7F7F) for _ in range(K)]
+    for k in range(K):
+        plan.kt_bucket_pack(-1, grads[k], peers[k])
+    outs = run_reduce(plan, peers, weights)
+    result = [torch.empty_like(t) for t in grads[0]]
+    plan.kt_bucket_unpack_scale(-1, outs, scale, result)
+    torch.cuda.synchronize()
+    hg = [[host(t) for t in g] for g in grads]
+    for k in range(K):
+        want = oracle.pack(L, hg[k], dtype)
+        for b in range(plan.num_buckets):
+            assert raw(host(peers[k][b])).tobytes() == raw(want[b]).tobytes(), (k, b)
+    refD = oracle.direct(hg, wts, scale, dtype, "D")
+    refS = oracle.direct(hg, wts, scale, dtype, "S")
+    gmax = max(float(np.abs(x).max()) for g in hg for x in g if x.size) if dtype == "f32" else 0.0
+    for t in range(len(w.numels)):
+        got = host(result[t])
+        assert_close(got, refD[t], dtype, gmax * abs(scale), "%s tensor %d" % (name, t))
+        assert raw(got).tobytes() == raw(refS[t]).tobytes(), "%s tensor %d strict" % (name, t)
+
+
+@pytest.mark.parametrize("name", ["mlp", "resnet18", "mobilenetv2"])
+def test_full_step_small_workloads(name):
+    full_step_check(name)
+    full_step_check(name, align=wl.WORKLOADS[name].elem_size, scale=0.37)
+
+
+def test_full_step_vit_b16():
+    full_step_check("vit_b16")

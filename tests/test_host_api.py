@@ -1,0 +1,207 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every declared symbol, plans shares and bucket layouts bit-identically to the
+CPU checker, builds a consistent tile table, and rejects bad arguments."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import oracle
+import paper_2505_10183_amd as kt
+from paper_2505_10183_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    names = []
+    for fn in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not fn.endswith(".h"):
+            continue
+        text = open(os.path.join(ROOT, "include", fn)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names += re.findall(r"\b(kt_[a-z_0-9]+)\s*\(", text)
+    return sorted(set(names))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"kt_plan_shares", "kt_bucket_pack", "kt_weighted_reduce", "kt_bucket_unpack_scale"} <= set(names)
+    L = kt.binding.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert b"gfx950" in L.kt_version()
+
+
+def test_no_checker_in_product_path():
+    """The GPU package never imports or mentions the CPU checker."""
+    pkg = os.path.join(ROOT, "paper_2505_10183_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, os.path.join(dirpath, f)
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2505_10183_amd" not in text and "libkt.so" not in text and "binding" not in text
+
+
+thr_lists = st.lists(st.floats(min_value=1e-3, max_value=1e3, allow_nan=False), min_size=1, max_size=16)
+
+
+@settings(max_examples=500, deadline=None)
+@given(thr=thr_lists, B=st.integers(0, 1 << 40))
+def test_shares_bit_exact_vs_checker(thr, B):
+    want = oracle.plan_shares(thr, B)
+    got, w = kt.kt_plan_shares(thr, B, want_weights=B > 0)
+    assert got == want
+    if B > 0:
+        ww = oracle.share_weights(want, B)
+        assert np.array(w, dtype=np.float32).tobytes() == ww.tobytes()
+
+
+def test_shares_workloads_and_golden():
+    for name in wl.WORKLOAD_ORDER:
+        w = wl.WORKLOADS[name]
+        got, wt = kt.kt_plan_shares(w.throughputs, w.global_batch)
+        assert got == oracle.plan_shares(w.throughputs, w.global_batch)
+        assert sum(got) == w.global_batch and abs(sum(wt) - 1.0) == 0.0
+    assert kt.kt_plan_shares([1.0, 0.7], 256)[0] == [151, 105]
+
+
+def test_shares_errors_leave_outputs_untouched():
+    L = kt.binding.lib()
+    thr = (ctypes.c_double * 2)(1.0, float("nan"))
+    b = (ctypes.c_int64 * 2)(-7, -7)
+    w = (ctypes.c_float * 2)(-7.0, -7.0)
+    assert L.kt_plan_shares(thr, 2, 10, b, w) == 1
+    assert list(b) == [-7, -7] and list(w) == [-7.0, -7.0]
+    assert b"finite" in L.kt_last_error()
+    good = (ctypes.c_double * 2)(1.0, 2.0)
+    for args in ((None, 2, 10, b, w), (good, 0, 10, b, w), (good, 65, 10, b, w), (good, 2, -1, b, w),
+                 (good, 2, (1 << 40) + 1, b, w), (good, 2, 0, b, w), (good, 2, 10, None, w)):
+        assert L.kt_plan_shares(*args) == 1
+        assert list(b) == [-7, -7]
+    neg = (ctypes.c_double * 2)(1.0, -2.0)
+    zero = (ctypes.c_double * 2)(0.0, 2.0)
+    inf = (ctypes.c_double * 2)(float("inf"), 2.0)
+    for t in (neg, zero, inf):
+        assert L.kt_plan_shares(t, 2, 10, b, None) == 1
+    assert L.kt_plan_shares(good, 2, 0, b, None) == 0 and list(b) == [0, 0]
+
+
+def layout_of(plan):
+    return {"tensor_bucket": [plan.tensor_info(t)[0] for t in range(plan.num_tensors)],
+            "tensor_offset": [plan.tensor_info(t)[1] for t in range(plan.num_tensors)],
+            "bucket_first": [plan.bucket_info(b)[1] for b in range(plan.num_buckets)],
+            "bucket_count": [plan.bucket_info(b)[2] for b in range(plan.num_buckets)],
+            "bucket_elems": [plan.bucket_info(b)[0] for b in range(plan.num_buckets)]}
+
+
+def check_tiles(plan, numels, es):
+    """Replay what a kernel workgroup assumes about its tile."""
+    E = 32768 // es
+    VE = 16 // es
+    L = layout_of(plan)
+    nb = plan.num_buckets
+    tiles = [plan.tile_info(i) for i in range(plan.num_tiles)]
+    # tiles enumerate every bucket in order with no gaps
+    i = 0
+    for b in range(nb):
+        n = L["bucket_elems"][b]
+        cnt = (n + E - 1) // E
+        for k in range(cnt):
+            tb, tk, t0, nt = tiles[i]
+            i += 1
+            assert (tb, tk) == (b, k)
+            s, e = k * E, min((k + 1) * E, n)
+            first, last = L["bucket_first"][b], L["bucket_first"][b] + L["bucket_count"][b] - 1
+            assert first <= t0 <= last and t0 + max(nt, 1) - 1 <= last
+            owners = [t for t in range(first, last + 1)
+                      if numels[t] > 0 and L["tensor_offset"][t] < e and L["tensor_offset"][t] + numels[t] > s]
+            if nt == 0:
+                assert owners == [t0]
+                assert L["tensor_offset"][t0] <= s and L["tensor_offset"][t0] + numels[t0] >= e
+                assert (e - s) % VE == 0
+            else:
+                assert all(t0 <= t < t0 + nt for t in owners)
+    assert i == len(tiles)
+
+
+@settings(max_examples=150, deadline=None)
+@given(numels=st.lists(st.one_of(st.integers(0, 40), st.integers(0, 30000)), min_size=0, max_size=30),
+       dtype=st.sampled_from(["f32", "bf16"]), cap=st.sampled_from([0, 64, 4096, 65536, 200000]),
+       lg=st.integers(0, 7))
+def test_layout_and_tiles_vs_checker(numels, dtype, cap, lg):
+    es = 4 if dtype == "f32" else 2
+    align = es << lg
+    plan = kt.Plan(numels, dtype, cap, align)
+    assert layout_of(plan) == oracle.assign_buckets(numels, es, cap, align)
+    check_tiles(plan, numels, es)
+    plan.close()
+
+
+def test_layout_workloads_vs_checker():
+    for name in wl.WORKLOAD_ORDER:
+        w = wl.WORKLOADS[name]
+        for align in (16, w.elem_size, 256):
+            plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, align)
+            assert layout_of(plan) == oracle.assign_buckets(w.numels, w.elem_size, w.bucket_cap_bytes, align)
+            plan.close()
+    for name in ("mlp", "resnet18", "mobilenetv2"):
+        w = wl.WORKLOADS[name]
+        plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+        check_tiles(plan, w.numels, w.elem_size)
+    r = wl.ragged_workload()
+    plan = kt.Plan(r.numels, r.dtype, r.bucket_cap_bytes, 16)
+    assert plan.num_buckets > 3
+    check_tiles(plan, r.numels, 4)
+
+
+def test_plan_argument_errors():
+    for args in (([1, 2], "f32", -1, 16), ([1, -2], "f32", 0, 16), ([1], "f32", 0, 3), ([1], "f32", 0, 2),
+                 ([1], "f32", 0, 8192), ([1], "bf16", 0, 1), ([1], "f32", 0, 24)):
+        with pytest.raises(kt.KtError) as ei:
+            kt.Plan(*args)
+        assert ei.value.status_name == "KT_EINVAL"
+    p = kt.Plan([], "f32", 0, 16)
+    assert p.num_buckets == 0 and p.num_tensors == 0 and p.num_tiles == 0
+    with pytest.raises(kt.KtError):
+        p.bucket_info(0)
+    with pytest.raises(kt.KtError):
+        p.tensor_info(0)
+    # nothing to do: returns before any GPU is touched
+    p.kt_bucket_pack(-1, [], [], stream=0)
+    p.kt_weighted_reduce(-1, [], 1, [1.0], [], stream=0)
+    p.kt_bucket_unpack_scale(-1, [], 1.0, [], stream=0)
+    L = kt.binding.lib()
+    assert L.kt_plan_destroy(None) == 0
+    assert L.kt_plan_num_buckets(None) == -1
+
+
+def test_device_call_argument_errors_without_gpu():
+    """Argument validation happens on the host before any GPU call."""
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    cases = [
+        (lambda: p.kt_bucket_pack(2, [16, 1600], [3200], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_pack(-1, [0, 1600], [3200], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_pack(-1, [16, 1600], [0], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_pack(-1, [18, 1600], [3200], stream=0), "KT_EALIGN"),
+        (lambda: p.kt_bucket_pack(-1, [16, 1600], [3202], stream=0), "KT_EALIGN"),
+        (lambda: p.kt_bucket_pack(-1, [3200, 1600], [3200], stream=0), "KT_EINVAL"),       # overlap
+        (lambda: p.kt_bucket_unpack_scale(-1, [3200], 1.0, [16, 3216], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_weighted_reduce(-1, [4096], 0, [], [8192], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_weighted_reduce(-1, [4096] * 65, 65, [1.0] * 65, [8192], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_weighted_reduce(-1, [4096, 0], 2, [1.0, 1.0], [8192], stream=0), "KT_EINVAL"),
+        (lambda: p.kt_weighted_reduce(-1, [4096, 4098], 2, [1.0, 1.0], [8192], stream=0), "KT_EALIGN"),
+        (lambda: p.kt_weighted_reduce(-1, [4096, 4160], 2, [1.0, 1.0], [4100], stream=0), "KT_EINVAL"),  # partial overlap
+        (lambda: p.kt_weighted_reduce(3, [4096, 4160], 2, [1.0, 1.0], [8192], stream=0), "KT_EINVAL"),
+    ]
+    for fn, want in cases:
+        with pytest.raises(kt.KtError) as ei:
+            fn()
+        assert ei.value.status_name == want, str(ei.value)
