@@ -1,9 +1,10 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU checker
 on the same seeded inputs.  Integer / index / copy work must be bit-exact;
 the fp32 reduce must satisfy |gpu - checker_D| <= 1e-6 * max|g| + 1e-9 (max
-over all K peer inputs of the bucket) and bf16 results must lie within one
-bf16 ulp of checker mode D; against checker mode S (same binary32 steps) the
-results are expected bit-identical."""
+over all K peer inputs of the bucket); bf16 results must lie within one bf16
+ulp of checker mode D after binary32 accumulation, i.e. within that same
+binary32 bound plus one bf16 spacing of the result; against checker mode S
+(the same binary32 steps) the results must be bit-identical."""
 import sys
 
 import numpy as np
@@ -39,12 +40,6 @@ def raw(a):
     return a.view(np.uint32) if a.dtype == np.float32 else a
 
 
-def bf16_ordered(bits):
-    """Map bf16 bit patterns to integers whose difference counts ulps."""
-    b = bits.astype(np.int32)
-    return np.where(b & 0x8000, -(b & 0x7FFF), b & 0x7FFF)
-
-
 def assert_close(got, want_D, dtype, gmax, what=""):
     if dtype == "f32":
         tol = 1e-6 * gmax + 1e-9
@@ -52,8 +47,18 @@ def assert_close(got, want_D, dtype, gmax, what=""):
         bad = ~(err <= tol)
         assert not bad.any(), "%s: max err %g > tol %g at %d" % (what, np.nanmax(err), tol, int(np.argmax(bad)))
     else:
-        d = np.abs(bf16_ordered(got) - bf16_ordered(want_D))
-        assert d.max() <= 1, "%s: %d bf16 ulps at %d" % (what, d.max(), int(np.argmax(d)))
+        # one bf16 ulp of the result on top of the binary32 accumulation bound
+        # (the latter matters only where the terms cancel and the result is tiny)
+        g = oracle.bf16_to_f32_array(got).astype(np.float64)
+        r = oracle.bf16_to_f32_array(want_D).astype(np.float64)
+        with np.errstate(divide="ignore"):
+            ex = np.floor(np.log2(np.maximum(np.abs(r), 2.0 ** -126)))
+        ulp = np.exp2(ex - 7)
+        tol = ulp + 1e-6 * gmax + 1e-9
+        err = np.abs(g - r)
+        both_nan = np.isnan(g) & np.isnan(r)
+        bad = ~((err <= tol) | both_nan | (g == r))
+        assert not bad.any(), "%s: err %g > tol %g at %d" % (what, err[bad][0], tol[bad][0], int(np.argmax(bad)))
 
 
 def alloc_buckets(plan, dtype, fill=None):
@@ -248,7 +253,7 @@ def test_reduce_vs_checker(dtype, K):
         if dtype == "f32":
             gmax = max(float(np.abs(x).max()) for x in hp)
         else:
-            gmax = 0.0
+            gmax = max(float(np.abs(oracle.bf16_to_f32_array(x)).max()) for x in hp)
         assert_close(got, wantD, dtype, gmax, "bucket %d" % b)
         assert raw(got).tobytes() == raw(wantS).tobytes(), "strict mode, bucket %d" % b
 
@@ -271,7 +276,9 @@ def test_reduce_identical_peers_and_integers(dtype):
         gmax = float(x.abs().max())
         assert_close(host(outs[0]), host(x), dtype, gmax, "identical peers")
     # integer-valued gradients, all-ones weights: exact integer sums
-    ints = [torch.randint(-64, 65, (n,), device=DEV, generator=torch.Generator(DEV).manual_seed(k)).to(tdtype(dtype))
+    # (bf16 holds integers exactly only up to 256: keep |sum| <= 8 * 16)
+    lim = 64 if dtype == "f32" else 16
+    ints = [torch.randint(-lim, lim + 1, (n,), device=DEV, generator=torch.Generator(DEV).manual_seed(k)).to(tdtype(dtype))
             for k in range(K)]
     outs = run_reduce(plan, [[t] for t in ints], [1.0] * K)
     ref = sum(t.to(torch.int64) for t in ints)
@@ -292,7 +299,7 @@ def test_reduce_identical_peers_and_integers(dtype):
 def test_reduce_in_place_and_misaligned_and_dense(dtype):
     K = 4
     es = 4 if dtype == "f32" else 2
-    numels = [33001, 7, 1, 40003]
+    numels = [33001, 7, 1, 40005]
     wts = oracle.share_weights([91, 73, 46, 46], 256)
     for align in (16, es):
         plan = kt.Plan(numels, dtype, 0, align)
@@ -377,7 +384,10 @@ def full_step_check(name, align=16, scale=1.0):
             assert raw(host(peers[k][b])).tobytes() == raw(want[b]).tobytes(), (k, b)
     refD = oracle.direct(hg, wts, scale, dtype, "D")
     refS = oracle.direct(hg, wts, scale, dtype, "S")
-    gmax = max(float(np.abs(x).max()) for g in hg for x in g if x.size) if dtype == "f32" else 0.0
+    if dtype == "f32":
+        gmax = max(float(np.abs(x).max()) for g in hg for x in g if x.size)
+    else:
+        gmax = max(float(np.abs(oracle.bf16_to_f32_array(x)).max()) for g in hg for x in g if x.size)
     for t in range(len(w.numels)):
         got = host(result[t])
         assert_close(got, refD[t], dtype, gmax * abs(scale), "%s tensor %d" % (name, t))
