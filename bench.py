@@ -165,6 +165,9 @@ def main():
     ap.add_argument("--also", default="vit_b16", help="comma list of further workloads reported for context")
     ap.add_argument("--cpu-elems", type=int, default=0, help="element budget of the CPU baseline sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
+                         "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
@@ -176,6 +179,15 @@ def main():
         sys.exit(1)
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.calibrate:
+        a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
 
     res, st = time_workload(args.workload, args.steps, args.warmup, dev)
     w = st["w"]

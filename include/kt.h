@@ -105,7 +105,7 @@ kt_status kt_plan_shares(const double *thr, int K, int64_t B,
  *                          element size gives dense packing.
  *   out          out     : new plan, to be released with kt_plan_destroy.
  * Errors: KT_EINVAL (arguments), KT_ENOMEM, KT_EUNSUPPORTED (the plan would
- * need 2^31 or more 32 KiB tiles).
+ * need 2^31 or more 16 KiB tiles).
  */
 kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt,
                          int64_t cap_bytes, int align_bytes, kt_plan **out);
@@ -130,9 +130,9 @@ kt_status kt_plan_tensor_info(const kt_plan *plan, int t, int *bucket,
 
 /*
  * Tile table introspection (for checks).  The device kernels process a bucket
- * in fixed tiles of 32 KiB, one workgroup each.  Tile i (0 <= i <
+ * in fixed tiles of 16 KiB, one workgroup each.  Tile i (0 <= i <
  * kt_plan_num_tiles) covers elements [tile_in_bucket * E, min((tile_in_bucket
- * + 1) * E, n_elems)) of `bucket`, E = 32768 / element size.  Tensors
+ * + 1) * E, n_elems)) of `bucket`, E = 16384 / element size.  Tensors
  * first_tensor .. first_tensor + n_tensors - 1 are the only ones that may own
  * elements of the tile; n_tensors == 0 marks a tile wholly inside tensor
  * first_tensor.  Out-pointers may be NULL.

@@ -9,7 +9,7 @@
 
 // A tile is a fixed-size slice of one bucket; one workgroup processes one tile.
 #ifndef KT_TILE_BYTES
-#define KT_TILE_BYTES 32768
+#define KT_TILE_BYTES 16384
 #endif
 #define KT_VEC_BYTES 16
 #define KT_TILE_VECS (KT_TILE_BYTES / KT_VEC_BYTES)

@@ -379,7 +379,7 @@ template <> __device__ __forceinline__ float narrow<float>(float a) { return a; 
 template <> __device__ __forceinline__ uint16_t narrow<uint16_t>(float a) { return (uint16_t)f32_to_bf16(a); }
 
 // Vectors in flight per lane before the first use (K loads each).
-template <int K> struct Unroll { static constexpr int U = K <= 2 ? 8 : (K <= 4 ? 4 : 2); };
+template <int K> struct Unroll { static constexpr int U = KT_TILE_VECS / KT_BLOCK; };
 
 template <typename T, int K>
 __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,

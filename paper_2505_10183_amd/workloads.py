@@ -139,7 +139,7 @@ def ragged_workload(name: str = "ragged", dtype: str = "f32", K: int = 3,
     """A small, deliberately awkward gradient set for parity tests.
 
     Sizes mix 1/3/5/7-element tensors, sizes straddling 16-byte vectors, sizes
-    a little above/below a 32 KiB tile, and a few tensors larger than the
+    a little above/below a kernel tile, and a few tensors larger than the
     bucket cap, so that a plan built from it spans several tiles per bucket,
     several buckets, ragged tails and an oversize bucket.
     """

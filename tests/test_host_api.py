@@ -104,7 +104,7 @@ def layout_of(plan):
 
 def check_tiles(plan, numels, es):
     """Replay what a kernel workgroup assumes about its tile."""
-    E = 32768 // es
+    E = 16384 // es
     VE = 16 // es
     L = layout_of(plan)
     nb = plan.num_buckets
