@@ -26,6 +26,24 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 
+# HBM bytes per launch of the reduce kernel from the FETCH_SIZE / WRITE_SIZE counter runs
+# summarised under profiles/ (reads scaled by the factor the 1 GiB calibration copy gives).
+# They describe the kernel sources with the digest below; after any change to those
+# sources the figure is reported as null until the counters are taken again.
+TRAFFIC_SOURCES_SHA = "b7ed61250625fc8a"
+TRAFFIC_BYTES = {"decoder_1p3b": 23704744643, "vit_b16": 3119112810}
+
+
+def measured_traffic(workload):
+    import hashlib
+    h = hashlib.sha256()
+    for f in ("kt_kernels.hip", "kt_internal.h"):
+        with open(os.path.join(ROOT, "paper_2505_10183_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    if h.hexdigest()[:16] != TRAFFIC_SOURCES_SHA:
+        return None
+    return TRAFFIC_BYTES.get(workload)
+
 
 def setup(name, dev):
     import torch
@@ -162,7 +180,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="decoder_1p3b")
-    ap.add_argument("--also", default="vit_b16", help="comma list of further workloads reported for context")
+    ap.add_argument("--also", default="vit_b16,resnet18,mobilenetv2,mlp",
+                    help="comma list of further workloads reported for context (the three small ones are "
+                         "cache-resident and launch-bound: not comparable with the HBM peak)")
     ap.add_argument("--cpu-elems", type=int, default=0, help="element budget of the CPU baseline sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
@@ -227,7 +247,8 @@ def main():
         "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone"))},
         "roofline": {"kernel": "kt_weighted_reduce (kt_reduce_kernel, K=%d, %s)" % (w.K, w.dtype),
                      "bound": "hbm", "achieved": round(res["reduce_GBps"], 2), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4), "traffic": None},
+                     "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4),
+                     "traffic": measured_traffic(w.name), "traffic_unit": "bytes per launch"},
         "cpu_baseline": cpu,
         "also": also,
     }
