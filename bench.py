@@ -74,6 +74,7 @@ def setup(name, dev):
         "a_local": plan.marshal(local), "a_slot0": plan.marshal(peers[0]),
         "a_peers": plan.marshal([peers[k][b] for b in range(nb) for k in range(K)]),
         "a_outs": plan.marshal(outs), "a_result": plan.marshal(result),
+        "a_others": plan.marshal([peers[k][b] for b in range(nb) for k in range(1, K)]),
     }
     import ctypes
     st["a_w"] = (ctypes.c_float * K)(*weights)
@@ -123,6 +124,10 @@ def time_workload(name, steps, warmup, dev):
     ms_pack = loop(lambda: p.kt_bucket_pack(-1, st["a_local"], st["a_slot0"]))
     ms_unpack = loop(lambda: p.kt_bucket_unpack_scale(-1, st["a_outs"], 1.0, st["a_result"]))
     ms_reduce_alone = loop(lambda: p.kt_weighted_reduce(-1, st["a_peers"], st["K"], st["a_w"], st["a_outs"]))
+    # the fused single pass (same results, (K+1)*s bytes per element): reported beside the
+    # chained step, never mixed into `value`
+    ms_fused = loop(lambda: p.kt_fused_step(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0,
+                                            st["a_result"]))
     e, s, K = w.total_elems, w.elem_size, st["K"]
     res = {
         "workload": name, "elements": e, "buckets": st["nb"], "K": K,
@@ -134,6 +139,8 @@ def time_workload(name, steps, warmup, dev):
         "reduce_ms_alone": ms_reduce_alone,
         "pack_ms": ms_pack, "pack_GBps": 2 * s * e / (ms_pack * 1e-3) / 1e9,
         "unpack_ms": ms_unpack, "unpack_GBps": 2 * s * e / (ms_unpack * 1e-3) / 1e9,
+        "fused_ms": ms_fused, "fused_GBps": (K + 1) * s * e / (ms_fused * 1e-3) / 1e9,
+        "fused_buckets_per_s": st["nb"] / (ms_fused * 1e-3),
     }
     return res, st
 
@@ -244,7 +251,7 @@ def main():
                    "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
         "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
         "buckets_per_s": round(res["buckets_per_s"], 1),
-        "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone"))},
+        "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone", "_per_s")) and k != "buckets_per_s"},
         "roofline": {"kernel": "kt_weighted_reduce (kt_reduce_kernel, K=%d, %s)" % (w.K, w.dtype),
                      "bound": "hbm", "achieved": round(res["reduce_GBps"], 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4),

@@ -191,6 +191,34 @@ kt_status kt_bucket_unpack_scale(kt_plan *plan, int bucket,
                                  const void *const *bucket_bufs, float scale,
                                  void *const *tensor_ptrs, void *stream);
 
+/*
+ * Fused single pass over the same data: for every tensor t of the selected
+ * bucket(s)
+ *     out_t[i] = scale * R( w_0 * local_t[i] + sum_{k=1}^{K-1} w_k * peer_{b,k}[off_t + i] )
+ * where R rounds the binary32 accumulator to the storage type (identity for
+ * fp32, nearest-even for bf16).  The local device's gradients (peer 0) are read
+ * in place from the tensors instead of being packed first, and the result goes
+ * straight to the output tensors: the arithmetic and its rounding order are
+ * those of kt_bucket_pack -> kt_weighted_reduce -> kt_bucket_unpack_scale, so
+ * results are bit-identical to that chain, while (K+1) instead of (K+5)
+ * element sizes move per element.  This is the form a DDP gradient hook wants
+ * (Sec. III: gradient AllReduce per bucket, followed by the copy back).
+ *
+ *   local_tensor_ptrs host, in: T device pointers, peer 0's gradients.
+ *   peer_bufs         host, in: device pointers, entry [b * (K-1) + (k-1)] =
+ *                               peer k's copy of bucket b, k = 1..K-1 (ignored
+ *                               when K == 1).
+ *   out_tensor_ptrs   host, in: T device pointers; out_t may be identical to
+ *                               local_t (in place); any other overlap with
+ *                               inputs is rejected where detected.
+ * Padding positions of the peer buckets are not read into any output.
+ */
+kt_status kt_fused_step(kt_plan *plan, int bucket,
+                        const void *const *local_tensor_ptrs,
+                        const void *const *peer_bufs, int K,
+                        const float *weights, float scale,
+                        void *const *out_tensor_ptrs, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

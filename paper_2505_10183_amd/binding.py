@@ -58,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_pack.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), vp]
         L.kt_weighted_reduce.argtypes = [vp, i32, c.POINTER(vp), i32, c.POINTER(c.c_float), c.POINTER(vp), vp]
         L.kt_bucket_unpack_scale.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), vp]
+        L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
+                                    c.POINTER(vp), vp]
+        L.kt_fused_step.restype = i32
         for n in ("kt_plan_shares", "kt_plan_create", "kt_plan_destroy", "kt_plan_bucket_info",
                   "kt_plan_tensor_info", "kt_bucket_pack", "kt_weighted_reduce", "kt_bucket_unpack_scale",
                   "kt_plan_num_buckets", "kt_plan_num_tensors"):
@@ -186,3 +189,15 @@ class Plan:
     def kt_bucket_unpack_scale(self, bucket: int, bucket_bufs, scale: float, tensors, stream=None):
         _check(lib().kt_bucket_unpack_scale(self._h, bucket, self._arr(bucket_bufs), float(scale),
                                             self._arr(tensors), _stream(stream)))
+
+    def kt_fused_step(self, bucket: int, local_tensors, peer_bufs, K: int, weights, scale: float, out_tensors,
+                      stream=None):
+        """peer_bufs: flat sequence over peers 1..K-1, entry [b * (K-1) + (k-1)]."""
+        if isinstance(weights, ctypes.Array):
+            w = weights
+        else:
+            if len(weights) != K:
+                raise ValueError("need K weights")
+            w = (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
+        _check(lib().kt_fused_step(self._h, bucket, self._arr(local_tensors), self._arr(peer_bufs), K, w,
+                                   float(scale), self._arr(out_tensors), _stream(stream)))

@@ -405,3 +405,66 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     if (e != 0) return hip_fail("kt_weighted_reduce: launch", (hipError_t)e);
     return mark_used(slot, s);
 }
+
+extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                                   const void *const *peer_bufs, int K, const float *weights, float scale,
+                                   void *const *out_tensor_ptrs, void *stream)
+{
+    const char *who = "kt_fused_step";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
+    if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int b0, b1;
+    int64_t tile0, ntiles;
+    kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
+    if (st != KT_OK || ntiles == 0) return st;
+    if (!local_tensor_ptrs || !out_tensor_ptrs || (K > 1 && !peer_bufs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    const KtHostPlan &hp = p->hp;
+    const size_t T = hp.t_numel.size(), nb = hp.b_elems.size(), KP = (size_t)(K - 1);
+    const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
+    // table layout: [local tensors T | output tensors T | peers nb*(K-1)]
+    std::vector<uint64_t> vals(2 * T + nb * KP, 0);
+    for (size_t t = 0; t < T; ++t) {
+        vals[t] = reinterpret_cast<uintptr_t>(local_tensor_ptrs[t]);
+        vals[T + t] = reinterpret_cast<uintptr_t>(out_tensor_ptrs[t]);
+    }
+    for (size_t i = 0; i < nb * KP; ++i) vals[2 * T + i] = reinterpret_cast<uintptr_t>(peer_bufs[i]);
+    bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
+    for (int b = b0; b < b1; ++b) {
+        const uintptr_t bbytes = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+        for (size_t k = 0; k < KP; ++k) {
+            const uintptr_t pp = vals[2 * T + (size_t)b * KP + k];
+            if (bbytes && !pp) { kt_set_error("%s: NULL peer %zu of bucket %d", who, k + 1, b); return KT_EINVAL; }
+            if (pp & emask) { kt_set_error("%s: peer %zu of bucket %d not aligned to the element size", who, k + 1, b); return KT_EALIGN; }
+            if (pp & (KT_VEC_BYTES - 1)) vec = false;
+        }
+        for (int t = hp.b_first[b]; t < hp.b_first[b] + hp.b_count[b]; ++t) {
+            const uintptr_t lp = vals[t], op = vals[T + t];
+            const uintptr_t tn = (uintptr_t)hp.t_numel[t] * hp.elem_size;
+            if (tn && (!lp || !op)) { kt_set_error("%s: NULL pointer for tensor %d", who, t); return KT_EINVAL; }
+            if ((lp | op) & emask) { kt_set_error("%s: tensor %d not aligned to the element size", who, t); return KT_EALIGN; }
+            // the output may be the local gradient itself (in place), never a partial overlap
+            if (tn && lp != op && lp < op + tn && op < lp + tn) { kt_set_error("%s: output %d partially overlaps its input", who, t); return KT_EINVAL; }
+            for (size_t k = 0; k < KP; ++k) {
+                const uintptr_t pp = vals[2 * T + (size_t)b * KP + k];
+                if (tn && op < pp + bbytes && pp < op + tn) { kt_set_error("%s: output %d overlaps peer %zu of bucket %d", who, t, k + 1, b); return KT_EINVAL; }
+            }
+        }
+    }
+    KtWeights w;
+    memset(&w, 0, sizeof w);
+    for (int k = 0; k < K; ++k) w.w[k] = weights[k];
+    st = ensure_device(p);
+    if (st != KT_OK) return st;
+    PtrSlot *slot = nullptr;
+    st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
+    if (st != KT_OK) return st;
+    const uint64_t *d = static_cast<const uint64_t *>(slot->dev);
+    int e = kt_launch_fused(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d),
+                            reinterpret_cast<const void *const *>(d + 2 * T), K, w, scale,
+                            reinterpret_cast<void *const *>(const_cast<uint64_t *>(d + T)), vec, stream);
+    if (e != 0) return hip_fail("kt_fused_step: launch", (hipError_t)e);
+    return mark_used(slot, s);
+}

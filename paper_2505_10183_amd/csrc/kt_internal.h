@@ -74,5 +74,16 @@ int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                      int64_t ntiles, const void *const *d_peer_ptrs, int K,
                      const KtWeights &w, void *const *d_out_ptrs,
                      bool vector_ok, void *stream);
+int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                    int64_t ntiles, const void *const *d_local_ptrs,
+                    const void *const *d_peer_ptrs, int K, const KtWeights &w,
+                    float scale, void *const *d_out_ptrs, bool vector_ok,
+                    void *stream);
+
+int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                    int64_t ntiles, const void *const *d_local_ptrs,
+                    const void *const *d_peer_ptrs, int K, const KtWeights &w,
+                    float scale, void *const *d_out_ptrs, bool vector_ok,
+                    void *stream);
 
 #endif

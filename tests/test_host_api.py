@@ -205,3 +205,22 @@ def test_device_call_argument_errors_without_gpu():
         with pytest.raises(kt.KtError) as ei:
             fn()
         assert ei.value.status_name == want, str(ei.value)
+
+
+def test_fused_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    ok_l, ok_o = [16, 1600], [32000, 48000]
+    cases = [
+        (lambda: p.kt_fused_step(-1, ok_l, [4096], 0, [], 1.0, ok_o, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_fused_step(5, ok_l, [4096], 2, [1.0, 1.0], 1.0, ok_o, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_fused_step(-1, [0, 1600], [4096], 2, [1.0, 1.0], 1.0, ok_o, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_fused_step(-1, ok_l, [0], 2, [1.0, 1.0], 1.0, ok_o, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_fused_step(-1, ok_l, [4098], 2, [1.0, 1.0], 1.0, ok_o, stream=0), "KT_EALIGN"),
+        (lambda: p.kt_fused_step(-1, [18, 1600], [4096], 2, [1.0, 1.0], 1.0, ok_o, stream=0), "KT_EALIGN"),
+        (lambda: p.kt_fused_step(-1, ok_l, [4096], 2, [1.0, 1.0], 1.0, [20, 48000], stream=0), "KT_EINVAL"),   # partial overlap with input
+        (lambda: p.kt_fused_step(-1, ok_l, [4096], 2, [1.0, 1.0], 1.0, [4100, 48000], stream=0), "KT_EINVAL"),  # overlaps a peer
+    ]
+    for fn, want in cases:
+        with pytest.raises(kt.KtError) as ei:
+            fn()
+        assert ei.value.status_name == want, str(ei.value)
