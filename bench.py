@@ -45,7 +45,7 @@ def measured_traffic(workload):
     return TRAFFIC_BYTES.get(workload)
 
 
-def setup(name, dev):
+def setup(name, dev, in_place=True):
     import torch
     import paper_2505_10183_amd as kt
     from paper_2505_10183_amd import workloads as wl
@@ -65,7 +65,9 @@ def setup(name, dev):
         torch.cuda.synchronize()
         del g
     local = wl.gradient_set(w, 0, dev)
-    outs = [torch.empty(n, dtype=td, device=dev) for n in elems]
+    # like an AllReduce, the reduce writes its result over peer slot 0 (the C ABI allows the
+    # output to be one of the inputs); --out-of-place gives it buffers of its own
+    outs = peers[0] if in_place else [torch.empty(n, dtype=td, device=dev) for n in elems]
     result = [torch.empty_like(t) for t in local]
     st = {
         "w": w, "plan": plan, "K": K, "weights": weights, "shares": shares, "nb": nb,
@@ -92,9 +94,9 @@ def step(st, scale=1.0, ev=None):
     p.kt_bucket_unpack_scale(-1, st["a_outs"], scale, st["a_result"])
 
 
-def time_workload(name, steps, warmup, dev):
+def time_workload(name, steps, warmup, dev, in_place=True):
     import torch
-    st = setup(name, dev)
+    st = setup(name, dev, in_place)
     w = st["w"]
     for _ in range(warmup):
         step(st)
@@ -192,6 +194,7 @@ def main():
                          "cache-resident and launch-bound: not comparable with the HBM peak)")
     ap.add_argument("--cpu-elems", type=int, default=0, help="element budget of the CPU baseline sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--out-of-place", action="store_true", help="reduce into separate output buffers")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -216,7 +219,7 @@ def main():
         del a, b
         torch.cuda.empty_cache()
 
-    res, st = time_workload(args.workload, args.steps, args.warmup, dev)
+    res, st = time_workload(args.workload, args.steps, args.warmup, dev, not args.out_of_place)
     w = st["w"]
     cpu = None
     if not args.no_cpu:
@@ -226,7 +229,7 @@ def main():
     del st
     torch.cuda.empty_cache()
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        r, s2 = time_workload(name, args.steps, args.warmup, dev)
+        r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place)
         also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         del s2
         torch.cuda.empty_cache()
@@ -247,7 +250,8 @@ def main():
         "config": {"workload": "%s: %d tensors, %d elements %s, K=%d, B=%d, %d buckets (cap %d MiB)"
                                % (w.name, len(w.shapes), w.total_elems, w.dtype, w.K, w.global_batch,
                                   res["buckets"], w.bucket_cap_bytes >> 20),
-                   "launch": "one batched launch per kernel over all buckets",
+                   "launch": "one batched launch per kernel over all buckets; reduce %s"
+                             % ("into its own output buffers" if args.out_of_place else "in place over peer slot 0"),
                    "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
         "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
         "buckets_per_s": round(res["buckets_per_s"], 1),

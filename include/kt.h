@@ -86,6 +86,33 @@ kt_status kt_plan_shares(const double *thr, int K, int64_t B,
                          int64_t *shares, float *weights);
 
 /*
+ * Load-adaptive sampler partition (Sec. III-C phase 2: portions of every
+ * global mini-batch go to device i in proportion to its score; Sec. IV-A: the
+ * DistributedSampler override).  Host only.
+ *
+ * The epoch ordering of the N dataset indices is the identity (shuffle == 0)
+ * or a Fisher-Yates shuffle (i = N-1..1, swap with a uniform j <= i) driven by
+ * SplitMix64 started at state seed + epoch * 0x9E3779B97F4A7C15, bounded draws
+ * by multiply-high with rejection.  The ordering is cut into global batches of
+ * B; in every batch device `rank` takes the contiguous slice of shares[rank]
+ * indices starting at shares[0] + ... + shares[rank-1].  If B does not divide
+ * N the last batch is dropped (drop_last != 0) or completed by wrapping around
+ * to the start of the ordering.
+ *
+ *   shares[K] host, in : integers >= 0 summing to B (e.g. from kt_plan_shares).
+ *   out       host, out: the rank's indices for the epoch, steps * shares[rank]
+ *                        entries; capacity is the size of `out` in entries.
+ *   count     host, out: entries written (may be NULL in kt_sampler_epoch).
+ * Errors: KT_EINVAL (arguments, capacity too small), KT_ENOMEM.
+ */
+kt_status kt_sampler_epoch_size(int64_t N, int64_t B, const int64_t *shares,
+                                int K, int rank, int drop_last, int64_t *count);
+kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
+                           uint64_t seed, uint64_t epoch, int shuffle, int rank,
+                           int drop_last, int64_t *out, int64_t capacity,
+                           int64_t *count);
+
+/*
  * Bucket plan: the flattening DDP applies before the gradient AllReduce
  * (Sec. III).  Host only until the first device call, which uploads the
  * plan's tables to the current device.

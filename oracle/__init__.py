@@ -276,3 +276,76 @@ def bf16_round(x: float) -> int:
 def bf16_to_f32_array(bits: np.ndarray) -> np.ndarray:
     """Exact widening of an array of bf16 bit patterns (numpy, no C)."""
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# --------------------------------------------------------------------------
+# Load-adaptive sampler partition (Sec. III-C phase 2: "allocates portions of
+# the global mini-batch to each device i based on its score"; Sec. IV-A: the
+# DistributedSampler override that takes per-device scores and distributes
+# dataset indices accordingly)
+# --------------------------------------------------------------------------
+
+_M64 = (1 << 64) - 1
+_GAMMA = 0x9E3779B97F4A7C15
+
+
+class SplitMix64:
+    """SplitMix64 (Steele, Lea, Flood 2014): state += gamma; output = mix(state)."""
+
+    def __init__(self, state: int):
+        self.state = state & _M64
+
+    def next(self) -> int:
+        self.state = (self.state + _GAMMA) & _M64
+        z = self.state
+        z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _M64
+        z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _M64
+        return z ^ (z >> 31)
+
+
+def _bounded(rng: SplitMix64, n: int) -> int:
+    """Unbiased integer in [0, n) from 64-bit draws (Lemire 2019: multiply,
+    take the high word, reject the few low words that would bias)."""
+    m = rng.next() * n
+    low = m & _M64
+    if low < n:
+        t = ((1 << 64) - n) % n
+        while low < t:
+            m = rng.next() * n
+            low = m & _M64
+    return m >> 64
+
+
+def epoch_permutation(N: int, seed: int, epoch: int, shuffle: bool = True) -> List[int]:
+    """The epoch's ordering of dataset indices: identity, or a Fisher-Yates
+    shuffle (i = N-1 .. 1, swap with a uniform j <= i) driven by SplitMix64
+    started at state seed + epoch * gamma."""
+    a = list(range(N))
+    if shuffle:
+        rng = SplitMix64(seed + epoch * _GAMMA)
+        for i in range(N - 1, 0, -1):
+            j = _bounded(rng, i + 1)
+            a[i], a[j] = a[j], a[i]
+    return a
+
+
+def sampler_epoch(N: int, B: int, shares: Sequence[int], seed: int, epoch: int,
+                  rank: int, shuffle: bool = True, drop_last: bool = False) -> List[int]:
+    """Dataset indices device ``rank`` processes in one epoch.
+
+    The epoch ordering is cut into global mini-batches of B indices; inside
+    every global batch device k takes the contiguous slice of b_k indices that
+    starts at b_0 + ... + b_{k-1}.  If N is not a multiple of B the last batch
+    is dropped (drop_last) or completed by wrapping around to the start of the
+    ordering (as torch's DistributedSampler pads)."""
+    K = len(shares)
+    if N < 0 or B < 1 or sum(shares) != B or any(b < 0 for b in shares) or not 0 <= rank < K:
+        raise ValueError("bad sampler arguments")
+    perm = epoch_permutation(N, seed, epoch, shuffle)
+    steps = N // B if drop_last else (N + B - 1) // B
+    start = sum(shares[:rank])
+    out = []
+    for s in range(steps):
+        for i in range(shares[rank]):
+            out.append(perm[(s * B + start + i) % N])
+    return out

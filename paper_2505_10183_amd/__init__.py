@@ -5,4 +5,4 @@ include/kt.h); ``binding`` marshals arguments, ``workloads`` describes the
 synthetic gradient sets.
 """
 from . import binding, workloads  # noqa: F401
-from .binding import Plan, KtError, kt_plan_shares  # noqa: F401
+from .binding import Plan, KtError, kt_plan_shares, kt_sampler_epoch  # noqa: F401

@@ -58,6 +58,11 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_pack.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), vp]
         L.kt_weighted_reduce.argtypes = [vp, i32, c.POINTER(vp), i32, c.POINTER(c.c_float), c.POINTER(vp), vp]
         L.kt_bucket_unpack_scale.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), vp]
+        L.kt_sampler_epoch_size.argtypes = [i64, i64, c.POINTER(i64), i32, i32, i32, c.POINTER(i64)]
+        L.kt_sampler_epoch_size.restype = i32
+        L.kt_sampler_epoch.argtypes = [i64, i64, c.POINTER(i64), i32, c.c_uint64, c.c_uint64, i32, i32, i32,
+                                       c.POINTER(i64), i64, c.POINTER(i64)]
+        L.kt_sampler_epoch.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -108,6 +113,20 @@ def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> T
     w = (ctypes.c_float * max(1, K))() if want_weights else None
     _check(lib().kt_plan_shares(t, K, int(B), b, w))
     return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
+
+
+def kt_sampler_epoch(N: int, B: int, shares: Sequence[int], seed: int, epoch: int, rank: int,
+                     shuffle: bool = True, drop_last: bool = False) -> List[int]:
+    """Dataset indices of device `rank` for one epoch."""
+    K = len(shares)
+    sh = (ctypes.c_int64 * max(1, K))(*[int(x) for x in shares])
+    n = ctypes.c_int64()
+    _check(lib().kt_sampler_epoch_size(int(N), int(B), sh, K, int(rank), int(drop_last), ctypes.byref(n)))
+    out = (ctypes.c_int64 * max(1, n.value))()
+    got = ctypes.c_int64()
+    _check(lib().kt_sampler_epoch(int(N), int(B), sh, K, int(seed) & ((1 << 64) - 1), int(epoch), int(shuffle),
+                                  int(rank), int(drop_last), out, n.value, ctypes.byref(got)))
+    return list(out[:got.value])
 
 
 class Plan:

@@ -224,3 +224,35 @@ def test_fused_argument_errors_without_gpu():
         with pytest.raises(kt.KtError) as ei:
             fn()
         assert ei.value.status_name == want, str(ei.value)
+
+
+@settings(max_examples=120, deadline=None)
+@given(N=st.integers(0, 3000), thr=st.lists(st.integers(1, 100).map(lambda v: v / 100.0), min_size=1, max_size=6),
+       B=st.integers(1, 300), seed=st.integers(0, 2 ** 64 - 1), epoch=st.integers(0, 1000),
+       shuffle=st.booleans(), drop_last=st.booleans())
+def test_sampler_bit_exact_vs_checker(N, thr, B, seed, epoch, shuffle, drop_last):
+    shares, _ = kt.kt_plan_shares(thr, B, want_weights=False)
+    for rank in range(len(thr)):
+        want = oracle.sampler_epoch(N, B, shares, seed, epoch, rank, shuffle, drop_last)
+        got = kt.kt_sampler_epoch(N, B, shares, seed, epoch, rank, shuffle, drop_last)
+        assert got == want
+
+
+def test_sampler_paper_setting_and_errors():
+    # the paper's run: CIFAR-10 (50 000 training images), global batch 256, scores (1.0, 0.7)
+    shares, _ = kt.kt_plan_shares([1.0, 0.7], 256)
+    a = kt.kt_sampler_epoch(50000, 256, shares, 5, 0, 0)
+    b = kt.kt_sampler_epoch(50000, 256, shares, 5, 0, 1)
+    assert len(a) == 196 * 151 and len(b) == 196 * 105
+    assert a == oracle.sampler_epoch(50000, 256, shares, 5, 0, 0)
+    assert b == oracle.sampler_epoch(50000, 256, shares, 5, 0, 1)
+    assert set(a) | set(b) == set(range(50000))
+    for args in ((10, 0, [1], 0, 0, 0), (10, 4, [3, 2], 0, 0, 0), (10, 4, [3, 1], 0, 0, 2), (-1, 4, [3, 1], 0, 0, 0),
+                 (10, 4, [5, -1], 0, 0, 0)):
+        with pytest.raises(kt.KtError):
+            kt.kt_sampler_epoch(*args)
+    L = kt.binding.lib()
+    sh = (ctypes.c_int64 * 2)(3, 1)
+    out = (ctypes.c_int64 * 4)(-9, -9, -9, -9)
+    assert L.kt_sampler_epoch(10, 4, sh, 2, 0, 0, 1, 0, 0, out, 4, None) == 1      # needs 9 entries
+    assert list(out) == [-9] * 4
