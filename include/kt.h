@@ -86,6 +86,25 @@ kt_status kt_plan_shares(const double *thr, int K, int64_t B,
                          int64_t *shares, float *weights);
 
 /*
+ * Weights for a two-level combination (Sec. III-A: reduction inside each group
+ * of homogeneous accelerators, then across groups through host memory).  Host
+ * only.  With B_g the sum of the shares of group g and B the sum of all shares:
+ *   w_intra[k] = (float)b_k / (float)B_g   (k's weight inside its group),
+ *   w_inter[g] = (float)B_g / (float)B     (the group's weight across groups),
+ * so that a group's result is the mean gradient over the group's samples and
+ * the product of the two weights is the flat weight b_k / B.  The two levels
+ * are two kt_weighted_reduce calls; the second one may read the other groups'
+ * results from device-accessible pinned host memory.
+ *
+ *   group_of[K]    host, in : group index of each device, in [0, G).
+ *   group_batch[G] host, out: optional (may be NULL), the B_g.
+ * Errors: KT_EINVAL (NULL, ranges, a group without samples).
+ */
+kt_status kt_plan_group_weights(const int64_t *shares, int K,
+                                const int *group_of, int G, float *w_intra,
+                                float *w_inter, int64_t *group_batch);
+
+/*
  * Load-adaptive sampler partition (Sec. III-C phase 2: portions of every
  * global mini-batch go to device i in proportion to its score; Sec. IV-A: the
  * DistributedSampler override).  Host only.
@@ -132,7 +151,7 @@ kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
  *                          element size gives dense packing.
  *   out          out     : new plan, to be released with kt_plan_destroy.
  * Errors: KT_EINVAL (arguments), KT_ENOMEM, KT_EUNSUPPORTED (the plan would
- * need 2^31 or more 16 KiB tiles).
+ * need 2^24 or more 16 KiB tiles, i.e. 256 GiB per peer).
  */
 kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt,
                          int64_t cap_bytes, int align_bytes, kt_plan **out);

@@ -72,6 +72,10 @@ def _c():
             fn = getattr(lib, name)
             fn.argtypes = [vp, i64, f32, vp]
             fn.restype = None
+        for name in ("kto_sgd_f32_D", "kto_sgd_f32_S", "kto_sgd_bf16_D", "kto_sgd_bf16_S"):
+            fn = getattr(lib, name)
+            fn.argtypes = [vp, i64, f32, vp, vp, f32, f32, f32, ctypes.c_int]
+            fn.restype = None
         lib.kto_bf16_widen.argtypes = [ctypes.c_uint16]
         lib.kto_bf16_widen.restype = ctypes.c_float
         lib.kto_bf16_round.argtypes = [ctypes.c_double]
@@ -349,3 +353,68 @@ def sampler_epoch(N: int, B: int, shares: Sequence[int], seed: int, epoch: int,
         for i in range(shares[rank]):
             out.append(perm[(s * B + start + i) % N])
     return out
+
+
+# --------------------------------------------------------------------------
+# Two-level combination (Sec. III-A: gradients are first reduced inside each
+# group of homogeneous accelerators, then the group results are combined
+# across groups through host memory)
+# --------------------------------------------------------------------------
+
+def group_weights(shares: Sequence[int], group_of: Sequence[int], G: int):
+    """Level 1: device k of group g weighs b_k / B_g (B_g = the group's samples),
+    so a group's result is the mean gradient over the group's samples.
+    Level 2: group g weighs B_g / B.  Both as single binary32 divisions.
+    The product (b_k/B_g)(B_g/B) = b_k/B is the flat weight."""
+    K = len(shares)
+    if len(group_of) != K or G < 1 or any(not 0 <= g < G for g in group_of):
+        raise ValueError("group_of")
+    Bg = [0] * G
+    for b, g in zip(shares, group_of):
+        Bg[g] += b
+    B = sum(shares)
+    if B <= 0 or any(x <= 0 for x in Bg):
+        raise ValueError("every group needs a positive share")
+    w1 = np.array([np.float32(b) / np.float32(Bg[g]) for b, g in zip(shares, group_of)], dtype=np.float32)
+    w2 = np.array([np.float32(x) / np.float32(B) for x in Bg], dtype=np.float32)
+    return w1, w2, Bg
+
+
+def two_level_reduce(peers: Sequence[np.ndarray], shares: Sequence[int], group_of: Sequence[int],
+                     G: int, dtype: str, mode: str = "D") -> np.ndarray:
+    """out = sum_g (B_g/B) * y_g with y_g = sum_{k in g} (b_k/B_g) x_k; each
+    level is a weighted_reduce (group members in ascending k, groups in
+    ascending g) and y_g is stored in the bucket's element type in between."""
+    w1, w2, _ = group_weights(shares, group_of, G)
+    ys = []
+    for g in range(G):
+        idx = [k for k in range(len(peers)) if group_of[k] == g]
+        ys.append(weighted_reduce([peers[k] for k in idx], w1[idx], dtype, mode))
+    return weighted_reduce(ys, w2, dtype, mode)
+
+
+# --------------------------------------------------------------------------
+# SGD with momentum and weight decay while unpacking (Sec. IV-B: the optimizer
+# of the paper's runs: momentum 0.9, weight decay 5e-4)
+# --------------------------------------------------------------------------
+
+def unpack_sgd(layout, buckets: Sequence[np.ndarray], numels: Sequence[int], scale: float,
+               params: Sequence[np.ndarray], momenta: Sequence[np.ndarray], lr: float, momentum: float,
+               weight_decay: float, first_step: bool, dtype: str, mode: str = "D"):
+    """For every tensor t and element i, with g = scale * bucket[off_t + i]:
+    g' = g + wd * p;  v' = g' on the first step, else mu * v + g';  p' = p - lr * v'.
+    Returns new (params, momenta) lists; inputs are not modified."""
+    new_p, new_v = [], []
+    fn = getattr(_c(), "kto_sgd_%s_%s" % (dtype, mode))
+    nd = _np_dtype(dtype)
+    for t, n in enumerate(numels):
+        o = layout["tensor_offset"][t]
+        x = np.ascontiguousarray(buckets[layout["tensor_bucket"][t]][o:o + n], dtype=nd)
+        p = np.array(params[t], dtype=np.float32).reshape(-1).copy()
+        v = np.array(momenta[t], dtype=np.float32).reshape(-1).copy()
+        assert p.size == n and v.size == n
+        fn(x.ctypes.data, n, ctypes.c_float(scale), p.ctypes.data, v.ctypes.data, ctypes.c_float(lr),
+           ctypes.c_float(momentum), ctypes.c_float(weight_decay), int(bool(first_step)))
+        new_p.append(p)
+        new_v.append(v)
+    return new_p, new_v

@@ -131,3 +131,61 @@ void kto_scale_bf16_S(const uint16_t *in, int64_t n, float scale,
         out[i] = kto_bf16_round((double)p);
     }
 }
+
+/* ---- SGD with momentum and weight decay applied while unpacking ----------
+ * The optimizer of the paper's training runs (Sec. IV-B: SGD, momentum 0.9,
+ * weight decay 5e-4), in the usual form: with gradient g = scale * bucket value,
+ *     g' = g + wd * p;   v' = g'  (first step)  or  mu * v + g';   p' = p - lr * v'.
+ * Parameters p and momentum v are binary32 and updated in place.
+ * D: each stored result (v', p') is the exact expression of the stored inputs,
+ *    evaluated in double, rounded once; p' uses the stored (rounded) v'.
+ * S: binary32 steps: g = scale*x (rounded), g' = fma(wd, p, g),
+ *    v' = fma(mu, v, g'), p' = fma(-lr, v', p).                              */
+
+void kto_sgd_f32_D(const float *x, int64_t n, float scale, float *p, float *v,
+                   float lr, float mu, float wd, int first)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double g = (double)scale * (double)x[i] + (double)wd * (double)p[i];
+        double vv = first ? g : (double)mu * (double)v[i] + g;
+        float vn = (float)vv;
+        p[i] = (float)((double)p[i] - (double)lr * (double)vn);
+        v[i] = vn;
+    }
+}
+
+void kto_sgd_f32_S(const float *x, int64_t n, float scale, float *p, float *v,
+                   float lr, float mu, float wd, int first)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float g = scale * x[i];
+        float g2 = fmaf(wd, p[i], g);
+        float vn = first ? g2 : fmaf(mu, v[i], g2);
+        p[i] = fmaf(-lr, vn, p[i]);
+        v[i] = vn;
+    }
+}
+
+void kto_sgd_bf16_D(const uint16_t *x, int64_t n, float scale, float *p, float *v,
+                    float lr, float mu, float wd, int first)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        double g = (double)scale * (double)kto_bf16_widen(x[i]) + (double)wd * (double)p[i];
+        double vv = first ? g : (double)mu * (double)v[i] + g;
+        float vn = (float)vv;
+        p[i] = (float)((double)p[i] - (double)lr * (double)vn);
+        v[i] = vn;
+    }
+}
+
+void kto_sgd_bf16_S(const uint16_t *x, int64_t n, float scale, float *p, float *v,
+                    float lr, float mu, float wd, int first)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        float g = scale * kto_bf16_widen(x[i]);
+        float g2 = fmaf(wd, p[i], g);
+        float vn = first ? g2 : fmaf(mu, v[i], g2);
+        p[i] = fmaf(-lr, vn, p[i]);
+        v[i] = vn;
+    }
+}

@@ -58,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_pack.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), vp]
         L.kt_weighted_reduce.argtypes = [vp, i32, c.POINTER(vp), i32, c.POINTER(c.c_float), c.POINTER(vp), vp]
         L.kt_bucket_unpack_scale.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), vp]
+        L.kt_plan_group_weights.argtypes = [c.POINTER(i64), i32, c.POINTER(i32), i32, c.POINTER(c.c_float),
+                                            c.POINTER(c.c_float), c.POINTER(i64)]
+        L.kt_plan_group_weights.restype = i32
         L.kt_sampler_epoch_size.argtypes = [i64, i64, c.POINTER(i64), i32, i32, i32, c.POINTER(i64)]
         L.kt_sampler_epoch_size.restype = i32
         L.kt_sampler_epoch.argtypes = [i64, i64, c.POINTER(i64), i32, c.c_uint64, c.c_uint64, i32, i32, i32,
@@ -113,6 +116,20 @@ def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> T
     w = (ctypes.c_float * max(1, K))() if want_weights else None
     _check(lib().kt_plan_shares(t, K, int(B), b, w))
     return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
+
+
+def kt_plan_group_weights(shares: Sequence[int], group_of: Sequence[int], G: int):
+    """(w_intra[K], w_inter[G], group_batch[G]) for a two-level combination."""
+    K = len(shares)
+    sh = (ctypes.c_int64 * max(1, K))(*[int(x) for x in shares])
+    go = (ctypes.c_int * max(1, K))(*[int(x) for x in group_of])
+    w1 = (ctypes.c_float * max(1, K))()
+    w2 = (ctypes.c_float * max(1, G))()
+    gb = (ctypes.c_int64 * max(1, G))()
+    if len(group_of) != K:
+        raise ValueError("group_of needs K entries")
+    _check(lib().kt_plan_group_weights(sh, K, go, int(G), w1, w2, gb))
+    return [float(w1[i]) for i in range(K)], [float(w2[i]) for i in range(G)], [int(gb[i]) for i in range(G)]
 
 
 def kt_sampler_epoch(N: int, B: int, shares: Sequence[int], seed: int, epoch: int, rank: int,

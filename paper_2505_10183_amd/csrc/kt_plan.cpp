@@ -50,6 +50,30 @@ extern "C" kt_status kt_plan_shares(const double *thr, int K, int64_t B, int64_t
     return KT_OK;
 }
 
+// Two-level weights (Sec. III-A): inside group g device k weighs b_k / B_g,
+// across groups group g weighs B_g / B.
+extern "C" kt_status kt_plan_group_weights(const int64_t *shares, int K, const int *group_of, int G,
+                                           float *w_intra, float *w_inter, int64_t *group_batch)
+{
+    if (!shares || !group_of || !w_intra || !w_inter) { kt_set_error("kt_plan_group_weights: NULL argument"); return KT_EINVAL; }
+    if (K < 1 || K > KT_MAX_PEERS || G < 1 || G > K) { kt_set_error("kt_plan_group_weights: need 1 <= G <= K <= %d", KT_MAX_PEERS); return KT_EINVAL; }
+    int64_t per_group[KT_MAX_PEERS] = {0};
+    int64_t total = 0;
+    for (int k = 0; k < K; ++k) {
+        if (group_of[k] < 0 || group_of[k] >= G) { kt_set_error("kt_plan_group_weights: group of device %d outside [0,%d)", k, G); return KT_EINVAL; }
+        if (shares[k] < 0 || shares[k] > ((int64_t)1 << 40)) { kt_set_error("kt_plan_group_weights: share %d out of range", k); return KT_EINVAL; }
+        per_group[group_of[k]] += shares[k];
+        total += shares[k];
+    }
+    for (int g = 0; g < G; ++g)
+        if (per_group[g] <= 0) { kt_set_error("kt_plan_group_weights: group %d has no samples", g); return KT_EINVAL; }
+    for (int k = 0; k < K; ++k) w_intra[k] = (float)shares[k] / (float)per_group[group_of[k]];
+    for (int g = 0; g < G; ++g) w_inter[g] = (float)per_group[g] / (float)total;
+    if (group_batch)
+        for (int g = 0; g < G; ++g) group_batch[g] = per_group[g];
+    return KT_OK;
+}
+
 static inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 kt_status kt_build_host_plan(const int64_t *numel, int T, kt_dtype dt, int64_t cap_bytes, int align_bytes,
@@ -106,7 +130,8 @@ kt_status kt_build_host_plan(const int64_t *numel, int T, kt_dtype dt, int64_t c
         const int64_t ntile = (hp.b_elems[b] + hp.tile_elems - 1) / hp.tile_elems;
         hp.b_tile0[b + 1] = hp.b_tile0[b] + ntile;
     }
-    if (hp.b_tile0[nb] >= ((int64_t)1 << 31)) { *msg = "more than 2^31 tiles"; return KT_EUNSUPPORTED; }
+    // one workgroup of KT_BLOCK lanes per tile; a dispatch holds fewer than 2^32 work-items
+    if (hp.b_tile0[nb] * KT_BLOCK >= ((int64_t)1 << 32)) { *msg = "plan too large: 2^24 or more tiles"; return KT_EUNSUPPORTED; }
     hp.tiles.resize((size_t)hp.b_tile0[nb]);
     const int VE = KT_VEC_BYTES / es;
     for (int b = 0; b < nb; ++b) {

@@ -475,3 +475,43 @@ def test_full_size_decoder_1p3b_sampled():
         b, off = L["tensor_bucket"][t], L["tensor_offset"][t]
         want = oracle.scale_array(host(outs[b][off:off + w.numels[t]]), 1.0, dtype, "S")
         assert host(result[t]).tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_two_level_reduce_with_pinned_host_inputs(dtype):
+    """Two groups of four devices: level 1 on the device, level 2 reads the
+    other group's result from pinned host memory (the stand-in for the host
+    relay between groups)."""
+    cfg = wl.WORKLOADS["vit_b16"]
+    K, G = 8, 2
+    group_of = [0, 0, 0, 0, 1, 1, 1, 1]
+    w = wl.ragged_workload(dtype=dtype, K=K, seed=88)
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    shares, flat_w = kt.kt_plan_shares(cfg.throughputs, cfg.global_batch)
+    w1, w2, gb = kt.kt_plan_group_weights(shares, group_of, G)
+    o1, o2, ob = oracle.group_weights(shares, group_of, G)
+    assert np.array(w1, np.float32).tobytes() == o1.tobytes() and np.array(w2, np.float32).tobytes() == o2.tobytes()
+    peers = [[wl.flat_normal(n, dtype, 1e-3, 300 * k + b, DEV) for b, n in enumerate(plan.bucket_elems())] for k in range(K)]
+    # level 1, group 0 (this device's group) and group 1 (computed here too, then "sent" to pinned host memory)
+    ys = []
+    for g in range(G):
+        idx = [k for k in range(K) if group_of[k] == g]
+        outs = [torch.empty_like(peers[0][b]) for b in range(nb)]
+        plan.kt_weighted_reduce(-1, [peers[k][b] for b in range(nb) for k in idx], len(idx), [w1[k] for k in idx], outs)
+        ys.append(outs)
+    torch.cuda.synchronize()
+    remote = [torch.empty(y.shape, dtype=y.dtype, pin_memory=True).copy_(y) for y in ys[1]]
+    torch.cuda.synchronize()
+    final = [torch.empty_like(peers[0][b]) for b in range(nb)]
+    plan.kt_weighted_reduce(-1, [t for b in range(nb) for t in (ys[0][b], remote[b])], G, w2, final)
+    torch.cuda.synchronize()
+    flat = oracle.share_weights(shares, cfg.global_batch)
+    for b in range(nb):
+        hp = [host(peers[k][b]) for k in range(K)]
+        want = oracle.two_level_reduce(hp, shares, group_of, G, dtype, "S")
+        got = host(final[b])
+        assert raw(got).tobytes() == raw(want).tobytes(), b
+        if dtype == "f32":   # and it agrees with the flat combination within the fp32 bound
+            gmax = max(float(np.abs(x).max()) for x in hp)
+            assert_close(got, oracle.weighted_reduce(hp, flat, dtype, "D"), dtype, gmax, "flat, bucket %d" % b)

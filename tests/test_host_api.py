@@ -256,3 +256,31 @@ def test_sampler_paper_setting_and_errors():
     out = (ctypes.c_int64 * 4)(-9, -9, -9, -9)
     assert L.kt_sampler_epoch(10, 4, sh, 2, 0, 0, 1, 0, 0, out, 4, None) == 1      # needs 9 entries
     assert list(out) == [-9] * 4
+
+
+def test_plan_too_large_is_rejected():
+    with pytest.raises(kt.KtError) as ei:
+        kt.Plan([1 << 36], "f32", 0, 16)          # 2^24 tiles of 4096 elements
+    assert ei.value.status_name == "KT_EUNSUPPORTED"
+    p = kt.Plan([(1 << 36) - 4096], "f32", 0, 16)
+    assert p.num_tiles == (1 << 24) - 1
+
+
+@settings(max_examples=200, deadline=None)
+@given(data=st.data(), K=st.integers(1, 12))
+def test_group_weights_bit_exact_vs_checker(data, K):
+    G = data.draw(st.integers(1, K))
+    shares = data.draw(st.lists(st.integers(1, 5000), min_size=K, max_size=K))
+    # every group non-empty: first G devices seed the groups
+    group_of = list(range(G)) + [data.draw(st.integers(0, G - 1)) for _ in range(K - G)]
+    w1, w2, gb = kt.kt_plan_group_weights(shares, group_of, G)
+    o1, o2, ob = oracle.group_weights(shares, group_of, G)
+    assert np.array(w1, np.float32).tobytes() == o1.tobytes()
+    assert np.array(w2, np.float32).tobytes() == o2.tobytes()
+    assert gb == ob
+
+
+def test_group_weights_errors():
+    for args in (([1, 2], [0, 2], 2), ([1, 2], [0, 0], 2), ([1, 2], [0, 1], 3), ([1, -2], [0, 1], 2), ([0, 0], [0, 0], 1)):
+        with pytest.raises(kt.KtError):
+            kt.kt_plan_group_weights(*args)

@@ -343,3 +343,123 @@ def test_bucketed_equals_unbucketed(dtype, mode):
         tol = 2e-6 if dtype == "f32" else 2.0 ** -7
         mag = scale * sum(abs(float(w[k])) * np.abs(xs[k]) for k in range(w_.K))
         assert np.all(np.abs(have - want) <= tol * mag + 1e-12)
+
+
+# ------------------------------------------------------------- two level --
+
+def test_group_weights_and_two_level_pins():
+    shares = [183, 183, 146, 146, 110, 110, 73, 73]            # ViT workload, B = 1024
+    group_of = [0, 0, 0, 0, 1, 1, 1, 1]
+    w1, w2, Bg = oracle.group_weights(shares, group_of, 2)
+    assert Bg == [658, 366] and sum(Bg) == 1024
+    flat = oracle.share_weights(shares, 1024)
+    for k in range(8):   # (b_k/B_g)(B_g/B) = b_k/B up to two roundings
+        assert abs(float(w1[k]) * float(w2[group_of[k]]) - float(flat[k])) <= 2.0 ** -23 * float(flat[k])
+    for g in range(2):   # level-1 weights of a group sum to one
+        assert abs(sum(float(w1[k]) for k in range(8) if group_of[k] == g) - 1.0) <= 4 * 2.0 ** -24
+    rng = np.random.default_rng(12)
+    xs = [(rng.standard_normal(5000) * 1e-3).astype(np.float32) for _ in range(8)]
+    flatD = oracle.weighted_reduce(xs, flat, "f32", "D").astype(np.float64)
+    gmax = max(float(np.abs(x).max()) for x in xs)
+    for mode in "DS":
+        two = oracle.two_level_reduce(xs, shares, group_of, 2, "f32", mode).astype(np.float64)
+        assert np.abs(two - flatD).max() <= 1e-6 * gmax + 1e-9
+    # identical peers: every level returns the input up to one rounding per level
+    two = oracle.two_level_reduce([xs[0]] * 8, shares, group_of, 2, "f32", "D")
+    assert np.abs(two.astype(np.float64) - xs[0]).max() <= 2 * 2.0 ** -24 * gmax
+    # power-of-two group sizes and integer data: exact
+    sh2 = [96, 32, 64, 64]
+    xi = rng.integers(-64, 65, size=(4, 2000))
+    got = oracle.two_level_reduce([xi[k].astype(np.float32) for k in range(4)], sh2, [0, 0, 1, 1], 2, "f32", "S")
+    num = (np.array(sh2)[:, None] * xi).sum(axis=0)
+    assert (got.astype(np.float64) * 256 == num).all()
+    # one group holding everything is the flat reduce
+    one = oracle.two_level_reduce(xs, shares, [0] * 8, 1, "f32", "S")
+    assert (one == oracle.weighted_reduce(xs, flat, "f32", "S")).all()
+    with pytest.raises(ValueError):
+        oracle.group_weights([1, 2], [0, 2], 2)
+    with pytest.raises(ValueError):
+        oracle.group_weights([1, 2], [0, 0], 2)
+
+
+# ------------------------------------------------------------------- SGD --
+
+def _one_tensor_layout(n):
+    return {"tensor_bucket": [0], "tensor_offset": [0], "bucket_elems": [n]}
+
+
+def test_sgd_against_torch_optimizer():
+    """Three steps of torch.optim.SGD(momentum=0.9, weight_decay=5e-4) on the CPU."""
+    rng = np.random.default_rng(21)
+    n = 4000
+    p0 = rng.standard_normal(n).astype(np.float32)
+    grads = [(rng.standard_normal(n) * 1e-2).astype(np.float32) for _ in range(3)]
+    lr, mu, wd = 0.1, 0.9, 5e-4
+    tp = torch.nn.Parameter(torch.from_numpy(p0.copy()))
+    opt = torch.optim.SGD([tp], lr=lr, momentum=mu, weight_decay=wd)
+    for mode in "DS":
+        tp.data.copy_(torch.from_numpy(p0))
+        opt.state.clear()
+        p, v = [p0.copy()], [np.zeros(n, np.float32)]
+        for step, g in enumerate(grads):
+            tp.grad = torch.from_numpy(g.copy())
+            opt.step()
+            p, v = oracle.unpack_sgd(_one_tensor_layout(n), [g], [n], 1.0, p, v, lr, mu, wd, step == 0, "f32", mode)
+            ref_p = tp.detach().numpy()
+            ref_v = opt.state[tp]["momentum_buffer"].numpy()
+            assert np.abs(v[0] - ref_v).max() <= 4 * 2.0 ** -24 * np.abs(ref_v).max()
+            assert np.abs(p[0] - ref_p).max() <= 2 * 2.0 ** -24 * np.abs(ref_p).max()
+
+
+def test_sgd_exact_on_dyadic_data():
+    """Small integers and power-of-two constants: every operation is exact, so
+    both modes equal rational arithmetic."""
+    rng = np.random.default_rng(22)
+    n = 500
+    x = rng.integers(-8, 9, n).astype(np.float32)
+    p0 = rng.integers(-8, 9, n).astype(np.float32)
+    v0 = rng.integers(-8, 9, n).astype(np.float32)
+    scale, lr, mu, wd = 0.5, 0.25, 0.5, 0.125
+    for first in (False, True):
+        for mode in "DS":
+            p, v = oracle.unpack_sgd(_one_tensor_layout(n), [x], [n], scale, [p0], [v0], lr, mu, wd, first, "f32", mode)
+            for i in range(n):
+                g = Fraction(scale) * Fraction(float(x[i])) + Fraction(wd) * Fraction(float(p0[i]))
+                vv = g if first else Fraction(mu) * Fraction(float(v0[i])) + g
+                pp = Fraction(float(p0[i])) - Fraction(lr) * vv
+                assert Fraction(float(v[0][i])) == vv and Fraction(float(p[0][i])) == pp
+
+
+def test_sgd_special_cases_and_modes():
+    rng = np.random.default_rng(23)
+    n = 3000
+    x = (rng.standard_normal(n) * 1e-3).astype(np.float32)
+    p0 = rng.standard_normal(n).astype(np.float32)
+    v0 = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    lay = _one_tensor_layout(n)
+    # no momentum, no decay: p' = p - lr * scale * x
+    p, v = oracle.unpack_sgd(lay, [x], [n], 2.0, [p0], [v0], 0.5, 0.0, 0.0, False, "f32", "D")
+    assert (v[0] == x * np.float32(2.0)).all()
+    assert (p[0] == (p0.astype(np.float64) - 0.5 * (2.0 * x.astype(np.float64))).astype(np.float32)).all()
+    # first step ignores the old momentum
+    a = oracle.unpack_sgd(lay, [x], [n], 1.0, [p0], [v0], 0.1, 0.9, 5e-4, True, "f32", "D")
+    b = oracle.unpack_sgd(lay, [x], [n], 1.0, [p0], [np.zeros(n, np.float32)], 0.1, 0.9, 5e-4, False, "f32", "D")
+    assert (a[0][0] == b[0][0]).all() and (a[1][0] == b[1][0]).all()
+    # inputs are not modified; D and S stay within a few roundings of each other
+    assert (p0 == p0.copy()).all()
+    d = oracle.unpack_sgd(lay, [x], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "f32", "D")
+    s = oracle.unpack_sgd(lay, [x], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "f32", "S")
+    assert np.abs(d[1][0] - s[1][0]).max() <= 3 * 2.0 ** -24 * np.abs(d[1][0]).max()
+    assert np.abs(d[0][0] - s[0][0]).max() <= 2 * 2.0 ** -24 * np.abs(d[0][0]).max()
+    # bf16 gradients are widened exactly: same as feeding the widened values as fp32
+    xb = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    for mode in "DS":
+        r16 = oracle.unpack_sgd(lay, [xb], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "bf16", mode)
+        r32 = oracle.unpack_sgd(lay, [oracle.bf16_to_f32_array(xb)], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "f32", mode)
+        assert (r16[0][0] == r32[0][0]).all() and (r16[1][0] == r32[1][0]).all()
+    # offsets: a tensor in the middle of a bucket reads its own slice
+    lay2 = {"tensor_bucket": [0, 0], "tensor_offset": [0, 8], "bucket_elems": [16]}
+    bucket = np.arange(16, dtype=np.float32)
+    pp, vv = oracle.unpack_sgd(lay2, [bucket], [5, 3], 1.0, [np.zeros(5, np.float32), np.zeros(3, np.float32)],
+                               [np.zeros(5, np.float32), np.zeros(3, np.float32)], 1.0, 0.0, 0.0, True, "f32", "S")
+    assert list(vv[0]) == [0, 1, 2, 3, 4] and list(vv[1]) == [8, 9, 10] and list(pp[1]) == [-8, -9, -10]
