@@ -265,6 +265,31 @@ kt_status kt_fused_step(kt_plan *plan, int bucket,
                         const float *weights, float scale,
                         void *const *out_tensor_ptrs, void *stream);
 
+/*
+ * Unpack fused with the optimizer of the paper's runs (Sec. IV-B: SGD with
+ * momentum 0.9 and weight decay 5e-4): the reduced gradient is consumed from
+ * the bucket and never written.  For every tensor t of the selected bucket(s)
+ * and element i, with g = scale * bucket_b[off_t + i] (one binary32 product;
+ * bf16 buckets are widened exactly first):
+ *     g' = fma(weight_decay, p, g)
+ *     v' = g'                       if first_step != 0
+ *          fma(momentum, v, g')     otherwise
+ *     p' = fma(-lr, v', p)
+ * p (parameters) and v (momentum) are binary32 tensors updated in place; on the
+ * first step v is written without being read.
+ *
+ *   param_ptrs, momentum_ptrs host, in: T device pointers each (binary32,
+ *                                       numel[t] elements), 4-byte aligned;
+ *                                       16-byte alignment gives the vector path.
+ * Parameters, momentum and buckets must not overlap.
+ */
+kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
+                               const void *const *bucket_bufs, float scale,
+                               void *const *param_ptrs,
+                               void *const *momentum_ptrs, float lr,
+                               float momentum, float weight_decay,
+                               int first_step, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -66,6 +66,9 @@ def lib() -> ctypes.CDLL:
         L.kt_sampler_epoch.argtypes = [i64, i64, c.POINTER(i64), i32, c.c_uint64, c.c_uint64, i32, i32, i32,
                                        c.POINTER(i64), i64, c.POINTER(i64)]
         L.kt_sampler_epoch.restype = i32
+        L.kt_bucket_unpack_sgd.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp), c.c_float,
+                                           c.c_float, c.c_float, i32, vp]
+        L.kt_bucket_unpack_sgd.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -237,3 +240,9 @@ class Plan:
             w = (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
         _check(lib().kt_fused_step(self._h, bucket, self._arr(local_tensors), self._arr(peer_bufs), K, w,
                                    float(scale), self._arr(out_tensors), _stream(stream)))
+
+    def kt_bucket_unpack_sgd(self, bucket: int, bucket_bufs, scale: float, params, momenta, lr: float,
+                             momentum: float, weight_decay: float, first_step: bool, stream=None):
+        _check(lib().kt_bucket_unpack_sgd(self._h, bucket, self._arr(bucket_bufs), float(scale), self._arr(params),
+                                          self._arr(momenta), float(lr), float(momentum), float(weight_decay),
+                                          int(bool(first_step)), _stream(stream)))

@@ -468,3 +468,55 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
     if (e != 0) return hip_fail("kt_fused_step: launch", (hipError_t)e);
     return mark_used(slot, s);
 }
+
+extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
+                                          void *const *param_ptrs, void *const *momentum_ptrs, float lr,
+                                          float momentum, float weight_decay, int first_step, void *stream)
+{
+    const char *who = "kt_bucket_unpack_sgd";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int b0, b1;
+    int64_t tile0, ntiles;
+    kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
+    if (st != KT_OK || ntiles == 0) return st;
+    if (!bucket_bufs || !param_ptrs || !momentum_ptrs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    const KtHostPlan &hp = p->hp;
+    const size_t T = hp.t_numel.size(), nb = hp.b_elems.size();
+    // table layout: [parameters T | momentum T | buckets nb]
+    std::vector<uint64_t> vals(2 * T + nb, 0);
+    for (size_t t = 0; t < T; ++t) {
+        vals[t] = reinterpret_cast<uintptr_t>(param_ptrs[t]);
+        vals[T + t] = reinterpret_cast<uintptr_t>(momentum_ptrs[t]);
+    }
+    for (size_t b = 0; b < nb; ++b) vals[2 * T + b] = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
+    bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
+    for (int b = b0; b < b1; ++b) {
+        const uintptr_t bp = vals[2 * T + b], bn = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+        if (bn && !bp) { kt_set_error("%s: NULL buffer for bucket %d", who, b); return KT_EINVAL; }
+        if (bp & ((uintptr_t)hp.elem_size - 1)) { kt_set_error("%s: bucket %d buffer not aligned to the element size", who, b); return KT_EALIGN; }
+        if (bp & (KT_VEC_BYTES - 1)) vec = false;
+        for (int t = hp.b_first[b]; t < hp.b_first[b] + hp.b_count[b]; ++t) {
+            const uintptr_t pp = vals[t], vp = vals[T + t], tn = (uintptr_t)hp.t_numel[t] * 4;
+            if (tn && (!pp || !vp)) { kt_set_error("%s: NULL parameter or momentum pointer for tensor %d", who, t); return KT_EINVAL; }
+            if ((pp | vp) & 3u) { kt_set_error("%s: tensor %d parameters/momentum not 4-byte aligned", who, t); return KT_EALIGN; }
+            if (tn && ((pp < vp + tn && vp < pp + tn) || (pp < bp + bn && bp < pp + tn) || (vp < bp + bn && bp < vp + tn))) {
+                kt_set_error("%s: parameters, momentum and bucket of tensor %d overlap", who, t);
+                return KT_EINVAL;
+            }
+        }
+    }
+    st = ensure_device(p);
+    if (st != KT_OK) return st;
+    PtrSlot *slot = nullptr;
+    st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
+    if (st != KT_OK) return st;
+    uint64_t *d = static_cast<uint64_t *>(slot->dev);
+    KtSgd a{scale, lr, momentum, weight_decay, first_step ? 1 : 0};
+    int e = kt_launch_unpack_sgd(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d + 2 * T),
+                                 reinterpret_cast<void *const *>(d), reinterpret_cast<void *const *>(d + T), a, vec,
+                                 stream);
+    if (e != 0) return hip_fail("kt_bucket_unpack_sgd: launch", (hipError_t)e);
+    return mark_used(slot, s);
+}

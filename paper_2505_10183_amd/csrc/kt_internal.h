@@ -86,4 +86,13 @@ int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                     float scale, void *const *d_out_ptrs, bool vector_ok,
                     void *stream);
 
+struct KtSgd {
+    float scale, lr, mu, wd;
+    int first;
+};
+int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                         int64_t ntiles, const void *const *d_bucket_ptrs,
+                         void *const *d_param_ptrs, void *const *d_mom_ptrs,
+                         const KtSgd &a, bool vector_ok, void *stream);
+
 #endif

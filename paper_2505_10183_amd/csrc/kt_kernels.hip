@@ -702,6 +702,193 @@ hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntile
     return hipGetLastError();
 }
 
+// ---- unpack fused with SGD (momentum, weight decay) -------------------------
+// With g = scale * bucket value:  g' = fma(wd, p, g);  v' = g' on the first
+// step, else fma(mu, v, g');  p' = fma(-lr, v', p).  p and v are binary32,
+// updated in place; the gradient itself is never written.
+
+__device__ __forceinline__ void sgd_elem(float x, float &p, float &v, const KtSgd &a)
+{
+    const float g = __fmul_rn(a.scale, x);
+    const float g2 = __fmaf_rn(a.wd, p, g);
+    const float vn = a.first ? g2 : __fmaf_rn(a.mu, v, g2);
+    p = __fmaf_rn(-a.lr, vn, p);
+    v = vn;
+}
+
+// one 16-byte gradient vector against its 4 (fp32) or 8 (bf16) parameters
+template <typename T> struct SgdVec;
+template <> struct SgdVec<float> {
+    static constexpr int PV = 1;
+    static __device__ __forceinline__ void apply(u32x4 g, u32x4 *p, u32x4 *v, const KtSgd &a)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float pp = __uint_as_float(p[0][c]), vv = __uint_as_float(v[0][c]);
+            sgd_elem(__uint_as_float(g[c]), pp, vv, a);
+            p[0][c] = __float_as_uint(pp);
+            v[0][c] = __float_as_uint(vv);
+        }
+    }
+};
+template <> struct SgdVec<uint16_t> {
+    static constexpr int PV = 2;
+    static __device__ __forceinline__ void apply(u32x4 g, u32x4 *p, u32x4 *v, const KtSgd &a)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int h = c >> 1, o = (c & 1) * 2;
+            float p0 = __uint_as_float(p[h][o]), v0 = __uint_as_float(v[h][o]);
+            float p1 = __uint_as_float(p[h][o + 1]), v1 = __uint_as_float(v[h][o + 1]);
+            sgd_elem(bf16_lo(g[c]), p0, v0, a);
+            sgd_elem(bf16_hi(g[c]), p1, v1, a);
+            p[h][o] = __float_as_uint(p0); v[h][o] = __float_as_uint(v0);
+            p[h][o + 1] = __float_as_uint(p1); v[h][o + 1] = __float_as_uint(v1);
+        }
+    }
+};
+
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                 const void *const *bucket_ptrs,
+                                                                 void *const *param_ptrs, void *const *mom_ptrs,
+                                                                 KtSgd a, int vec_ok)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int PV = SgdVec<T>::PV;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    __shared__ LdsTable2 lds;
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const T *src = reinterpret_cast<const T *>(bucket_ptrs[g.bucket]);
+    const int tid = threadIdx.x;
+
+    if (vec_ok && tl.nt == 0) {
+        const int64_t rel = g.start - tb.t_off[tl.t0];
+        float *pp = reinterpret_cast<float *>(param_ptrs[tl.t0]) + rel;
+        float *vp = reinterpret_cast<float *>(mom_ptrs[tl.t0]) + rel;
+        if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0) {
+            const u32x4 *s4 = reinterpret_cast<const u32x4 *>(src + g.start);
+            u32x4 *p4 = reinterpret_cast<u32x4 *>(pp);
+            u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
+            const int nvec = (int)((g.end - g.start) / VE);
+            if (nvec == KT_TILE_VECS) {
+                u32x4 gr[VPT], pr[VPT][PV], vr[VPT][PV];
+#pragma unroll
+                for (int u = 0; u < VPT; ++u) {
+                    const int idx = u * KT_BLOCK + tid;
+                    gr[u] = ld_vec(s4 + idx);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        pr[u][h] = ld_vec(p4 + idx * PV + h);
+                        vr[u][h] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[u][h] = ld_vec(v4 + idx * PV + h);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < VPT; ++u) {
+                    const int idx = u * KT_BLOCK + tid;
+                    SgdVec<T>::apply(gr[u], pr[u], vr[u], a);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        st_vec(p4 + idx * PV + h, pr[u][h]);
+                        st_vec(v4 + idx * PV + h, vr[u][h]);
+                    }
+                }
+            } else {
+#pragma unroll 1
+                for (int idx = tid; idx < nvec; idx += KT_BLOCK) {
+                    u32x4 pr[PV], vr[PV];
+                    const u32x4 gr = ld_vec(s4 + idx);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        pr[h] = ld_vec(p4 + idx * PV + h);
+                        vr[h] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[h] = ld_vec(v4 + idx * PV + h);
+                    }
+                    SgdVec<T>::apply(gr, pr, vr, a);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        st_vec(p4 + idx * PV + h, pr[h]);
+                        st_vec(v4 + idx * PV + h, vr[h]);
+                    }
+                }
+            }
+            return;
+        }
+    }
+
+    const int nt = tl.nt == 0 ? 1 : tl.nt;
+    const int64_t *t_off;
+    const int64_t *t_numel;
+    const uintptr_t *t_p;
+    const uintptr_t *t_v;
+    if (nt <= KT_LDS_TENSORS) {
+        for (int i = tid; i < nt; i += KT_BLOCK) {
+            lds.off[i] = tb.t_off[tl.t0 + i];
+            lds.numel[i] = tb.t_numel[tl.t0 + i];
+            lds.src[i] = reinterpret_cast<uintptr_t>(param_ptrs[tl.t0 + i]);
+            lds.dst[i] = reinterpret_cast<uintptr_t>(mom_ptrs[tl.t0 + i]);
+        }
+        __syncthreads();
+        t_off = lds.off; t_numel = lds.numel; t_p = lds.src; t_v = lds.dst;
+    } else {
+        t_off = tb.t_off + tl.t0; t_numel = tb.t_numel + tl.t0;
+        t_p = reinterpret_cast<const uintptr_t *>(param_ptrs) + tl.t0;
+        t_v = reinterpret_cast<const uintptr_t *>(mom_ptrs) + tl.t0;
+    }
+    TableView tv;
+    tv.off = t_off; tv.numel = t_numel; tv.ptr = t_p;
+
+    const int64_t b_n = tb.b_elems[g.bucket];
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+    for (int v = tid; v < nvec; v += KT_BLOCK) {
+        const int64_t e0 = g.start + (int64_t)v * VE;
+        int i = find_owner(tv, nt, e0);
+        if (vec_ok && i >= 0 && e0 + VE <= b_n) {
+            const int64_t r = e0 - t_off[i];
+            if (r + VE <= t_numel[i]) {
+                const uintptr_t pa = t_p[i] + (uintptr_t)r * 4, va = t_v[i] + (uintptr_t)r * 4;
+                if (((pa | va) & 15u) == 0) {
+                    u32x4 pr[PV], vr[PV];
+                    const u32x4 gr = ld_vec(src + e0);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        pr[h] = ld_vec(reinterpret_cast<const u32x4 *>(pa) + h);
+                        vr[h] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[h] = ld_vec(reinterpret_cast<const u32x4 *>(va) + h);
+                    }
+                    SgdVec<T>::apply(gr, pr, vr, a);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
+                        st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
+                    }
+                    continue;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int q = 0; q < VE; ++q) {
+            const int64_t e = e0 + q;
+            if (e >= b_n) break;
+            while (i + 1 < nt && t_off[i + 1] <= e) ++i;
+            if (i >= 0 && e - t_off[i] < t_numel[i]) {
+                const int64_t r = e - t_off[i];
+                float *pe = reinterpret_cast<float *>(t_p[i]) + r;
+                float *ve = reinterpret_cast<float *>(t_v[i]) + r;
+                float pv = ld_elem(pe), vv = a.first ? 0.0f : ld_elem(ve);
+                sgd_elem(widen(ld_elem(src + e)), pv, vv, a);
+                st_elem(pe, pv);
+                st_elem(ve, vv);
+            }
+        }
+    }
+}
+
 }  // namespace
 
 int kt_launch_pack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
@@ -752,4 +939,17 @@ int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_
     if (dt == KT_F32)
         return (int)launch_fused_t<float>(tb, tile0, ntiles, d_local_ptrs, d_peer_ptrs, K, w, scale, d_out_ptrs, vector_ok, s);
     return (int)launch_fused_t<uint16_t>(tb, tile0, ntiles, d_local_ptrs, d_peer_ptrs, K, w, scale, d_out_ptrs, vector_ok, s);
+}
+
+int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                         const void *const *d_bucket_ptrs, void *const *d_param_ptrs, void *const *d_mom_ptrs,
+                         const KtSgd &a, bool vector_ok, void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (dt == KT_F32)
+        kt_unpack_sgd_kernel<float><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+    else
+        kt_unpack_sgd_kernel<uint16_t><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+    return (int)hipGetLastError();
 }

@@ -284,3 +284,21 @@ def test_group_weights_errors():
     for args in (([1, 2], [0, 2], 2), ([1, 2], [0, 0], 2), ([1, 2], [0, 1], 3), ([1, -2], [0, 1], 2), ([0, 0], [0, 0], 1)):
         with pytest.raises(kt.KtError):
             kt.kt_plan_group_weights(*args)
+
+
+def test_unpack_sgd_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    ok_p, ok_v, ok_b = [16000, 32000], [48000, 64000], [4096]
+    cases = [
+        (lambda: p.kt_bucket_unpack_sgd(3, ok_b, 1.0, ok_p, ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, [0], 1.0, ok_p, ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, ok_b, 1.0, [0, 32000], ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, ok_b, 1.0, [16002, 32000], ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EALIGN"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, [4098], 1.0, ok_p, ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EALIGN"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, ok_b, 1.0, ok_p, [16008, 64000], 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_unpack_sgd(-1, ok_b, 1.0, [4100, 32000], ok_v, 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+    ]
+    for fn, want in cases:
+        with pytest.raises(kt.KtError) as ei:
+            fn()
+        assert ei.value.status_name == want, str(ei.value)
