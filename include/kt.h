@@ -86,6 +86,24 @@ kt_status kt_plan_shares(const double *thr, int K, int64_t B,
                          int64_t *shares, float *weights);
 
 /*
+ * Online adaptation of the shares (Sec. III-C phase 1, "Online Adaptation":
+ * monitor the computation time per batch during training and adjust the
+ * scores).  Host only.  Device k processed shares_used[k] samples in
+ * step_time[k] (any time unit); its time per sample tau_k = t_k / b_k enters
+ *     ema[k] <- alpha * tau_k + (1 - alpha) * ema[k]
+ * (ema[k] <= 0 means "no estimate yet" and is replaced by tau_k; a device that
+ * processed no samples keeps its estimate), all in IEEE double.  The new
+ * shares are kt_plan_shares(1 / ema, B); weights as there (may be NULL).
+ *   ema[K] host, in/out; alpha in (0, 1].
+ * Errors: KT_EINVAL (NULL, ranges, a device with samples but a time that is
+ * not finite and positive, a device without any estimate); on error nothing
+ * is written.
+ */
+kt_status kt_replan_shares(const double *step_time, const int64_t *shares_used,
+                           double *ema, double alpha, int K, int64_t B,
+                           int64_t *shares, float *weights);
+
+/*
  * Weights for a two-level combination (Sec. III-A: reduction inside each group
  * of homogeneous accelerators, then across groups through host memory).  Host
  * only.  With B_g the sum of the shares of group g and B the sum of all shares:

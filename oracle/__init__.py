@@ -418,3 +418,34 @@ def unpack_sgd(layout, buckets: Sequence[np.ndarray], numels: Sequence[int], sca
         new_p.append(p)
         new_v.append(v)
     return new_p, new_v
+
+
+# --------------------------------------------------------------------------
+# Online adaptation of the scores (Sec. III-C phase 1, "Online Adaptation":
+# monitor computation time per batch during training and adjust the scores)
+# --------------------------------------------------------------------------
+
+def replan_shares(step_time: Sequence[float], shares_used: Sequence[int],
+                  ema: Sequence[float], alpha: float, B: int):
+    """One adaptation step.  Device k processed shares_used[k] samples in
+    step_time[k]; its time per sample tau_k = t_k / b_k enters an exponential
+    moving average  ema_k <- alpha * tau_k + (1 - alpha) * ema_k  (ema_k <= 0
+    means "no estimate yet" and is replaced by tau_k; a device that processed
+    no samples keeps its estimate).  The score is the speed 1 / ema_k and the
+    new shares are plan_shares(1 / ema, B).  Returns (new_ema, shares)."""
+    K = len(step_time)
+    if len(shares_used) != K or len(ema) != K or not (0.0 < alpha <= 1.0):
+        raise ValueError("bad arguments")
+    new = []
+    for t, b, e in zip(step_time, shares_used, ema):
+        e = float(e)
+        if b > 0:
+            if not (math.isfinite(t) and t > 0.0):
+                raise ValueError("step times must be finite and > 0")
+            tau = float(t) / float(b)
+            e = tau if not e > 0.0 else alpha * tau + (1.0 - alpha) * e
+        if not (e > 0.0 and math.isfinite(e)):
+            raise ValueError("no speed estimate for a device")
+        new.append(e)
+    thr = [1.0 / e for e in new]
+    return new, plan_shares(thr, B)

@@ -5,5 +5,5 @@ include/kt.h); ``binding`` marshals arguments, ``workloads`` describes the
 synthetic gradient sets.
 """
 from . import binding, workloads  # noqa: F401
-from .binding import (Plan, KtError, kt_plan_shares, kt_plan_group_weights,  # noqa: F401
+from .binding import (Plan, KtError, kt_plan_shares, kt_plan_group_weights, kt_replan_shares,  # noqa: F401
                       kt_sampler_epoch)

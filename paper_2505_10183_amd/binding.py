@@ -58,6 +58,9 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_pack.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), vp]
         L.kt_weighted_reduce.argtypes = [vp, i32, c.POINTER(vp), i32, c.POINTER(c.c_float), c.POINTER(vp), vp]
         L.kt_bucket_unpack_scale.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), vp]
+        L.kt_replan_shares.argtypes = [c.POINTER(c.c_double), c.POINTER(i64), c.POINTER(c.c_double), c.c_double, i32,
+                                       i64, c.POINTER(i64), c.POINTER(c.c_float)]
+        L.kt_replan_shares.restype = i32
         L.kt_plan_group_weights.argtypes = [c.POINTER(i64), i32, c.POINTER(i32), i32, c.POINTER(c.c_float),
                                             c.POINTER(c.c_float), c.POINTER(i64)]
         L.kt_plan_group_weights.restype = i32
@@ -119,6 +122,21 @@ def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> T
     w = (ctypes.c_float * max(1, K))() if want_weights else None
     _check(lib().kt_plan_shares(t, K, int(B), b, w))
     return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
+
+
+def kt_replan_shares(step_time: Sequence[float], shares_used: Sequence[int], ema: Sequence[float], alpha: float,
+                     B: int):
+    """One online-adaptation step: (new_ema, shares, weights)."""
+    K = len(step_time)
+    if len(shares_used) != K or len(ema) != K:
+        raise ValueError("need K entries each")
+    t = (ctypes.c_double * max(1, K))(*[float(x) for x in step_time])
+    u = (ctypes.c_int64 * max(1, K))(*[int(x) for x in shares_used])
+    e = (ctypes.c_double * max(1, K))(*[float(x) for x in ema])
+    b = (ctypes.c_int64 * max(1, K))()
+    w = (ctypes.c_float * max(1, K))()
+    _check(lib().kt_replan_shares(t, u, e, float(alpha), K, int(B), b, w if B > 0 else None))
+    return [float(e[i]) for i in range(K)], [int(b[i]) for i in range(K)], [float(w[i]) for i in range(K)]
 
 
 def kt_plan_group_weights(shares: Sequence[int], group_of: Sequence[int], G: int):

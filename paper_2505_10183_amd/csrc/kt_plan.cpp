@@ -50,6 +50,40 @@ extern "C" kt_status kt_plan_shares(const double *thr, int K, int64_t B, int64_t
     return KT_OK;
 }
 
+// Online adaptation (Sec. III-C phase 1): exponential moving average of the
+// measured time per sample of every device, then the shares for speeds 1/ema.
+extern "C" kt_status kt_replan_shares(const double *step_time, const int64_t *shares_used, double *ema, double alpha,
+                                      int K, int64_t B, int64_t *shares, float *weights)
+{
+    if (!step_time || !shares_used || !ema || !shares) { kt_set_error("kt_replan_shares: NULL argument"); return KT_EINVAL; }
+    if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("kt_replan_shares: K=%d outside [1,%d]", K, KT_MAX_PEERS); return KT_EINVAL; }
+    if (!(alpha > 0.0 && alpha <= 1.0)) { kt_set_error("kt_replan_shares: alpha outside (0,1]"); return KT_EINVAL; }
+    double next[KT_MAX_PEERS], speed[KT_MAX_PEERS];
+    for (int k = 0; k < K; ++k) {
+        double e = ema[k];
+        if (shares_used[k] < 0) { kt_set_error("kt_replan_shares: negative sample count for device %d", k); return KT_EINVAL; }
+        if (shares_used[k] > 0) {
+            if (!(std::isfinite(step_time[k]) && step_time[k] > 0.0)) {
+                kt_set_error("kt_replan_shares: step time of device %d is not finite and positive", k);
+                return KT_EINVAL;
+            }
+            const double tau = step_time[k] / (double)shares_used[k];
+            e = !(e > 0.0) ? tau : alpha * tau + (1.0 - alpha) * e;
+        }
+        if (!(e > 0.0 && std::isfinite(e))) { kt_set_error("kt_replan_shares: no speed estimate for device %d", k); return KT_EINVAL; }
+        next[k] = e;
+        speed[k] = 1.0 / e;
+    }
+    int64_t b[KT_MAX_PEERS];
+    float w[KT_MAX_PEERS];
+    kt_status st = kt_plan_shares(speed, K, B, b, weights ? w : nullptr);
+    if (st != KT_OK) return st;
+    for (int k = 0; k < K; ++k) { ema[k] = next[k]; shares[k] = b[k]; }
+    if (weights)
+        for (int k = 0; k < K; ++k) weights[k] = w[k];
+    return KT_OK;
+}
+
 // Two-level weights (Sec. III-A): inside group g device k weighs b_k / B_g,
 // across groups group g weighs B_g / B.
 extern "C" kt_status kt_plan_group_weights(const int64_t *shares, int K, const int *group_of, int G,

@@ -302,3 +302,34 @@ def test_unpack_sgd_argument_errors_without_gpu():
         with pytest.raises(kt.KtError) as ei:
             fn()
         assert ei.value.status_name == want, str(ei.value)
+
+
+@settings(max_examples=300, deadline=None)
+@given(data=st.data(), K=st.integers(1, 8), B=st.integers(1, 5000),
+       alpha=st.floats(min_value=0.01, max_value=1.0))
+def test_replan_bit_exact_vs_checker(data, K, B, alpha):
+    times = data.draw(st.lists(st.floats(min_value=1e-3, max_value=1e3), min_size=K, max_size=K))
+    used = data.draw(st.lists(st.integers(0, 500), min_size=K, max_size=K))
+    ema = data.draw(st.lists(st.one_of(st.just(0.0), st.floats(min_value=1e-4, max_value=10.0)), min_size=K, max_size=K))
+    try:
+        want_e, want_s = oracle.replan_shares(times, used, ema, alpha, B)
+    except ValueError:
+        with pytest.raises(kt.KtError):
+            kt.kt_replan_shares(times, used, ema, alpha, B)
+        return
+    got_e, got_s, got_w = kt.kt_replan_shares(times, used, ema, alpha, B)
+    assert got_e == want_e and got_s == want_s
+    assert np.array(got_w, np.float32).tobytes() == oracle.share_weights(want_s, B).tobytes()
+
+
+def test_replan_errors_leave_state_untouched():
+    L = kt.binding.lib()
+    t = (ctypes.c_double * 2)(1.0, float("nan"))
+    u = (ctypes.c_int64 * 2)(4, 4)
+    e = (ctypes.c_double * 2)(0.5, 0.5)
+    b = (ctypes.c_int64 * 2)(-7, -7)
+    assert L.kt_replan_shares(t, u, e, 0.5, 2, 8, b, None) == 1
+    assert list(e) == [0.5, 0.5] and list(b) == [-7, -7]
+    t2 = (ctypes.c_double * 2)(1.0, 1.0)
+    assert L.kt_replan_shares(t2, u, e, 0.0, 2, 8, b, None) == 1
+    assert L.kt_replan_shares(t2, u, e, 0.5, 2, 8, b, None) == 0 and sum(b) == 8
