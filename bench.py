@@ -130,6 +130,13 @@ def time_workload(name, steps, warmup, dev, in_place=True):
     # chained step, never mixed into `value`
     ms_fused = loop(lambda: p.kt_fused_step(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0,
                                             st["a_result"]))
+    # unpack fused with SGD momentum / weight decay: reads the bucket, p and v, writes p and v
+    import torch as _t
+    params = [_t.zeros(t.numel(), dtype=_t.float32, device=dev) for t in st["local"]]
+    moms = [_t.zeros(t.numel(), dtype=_t.float32, device=dev) for t in st["local"]]
+    a_p, a_v = p.marshal(params), p.marshal(moms)
+    ms_sgd = loop(lambda: p.kt_bucket_unpack_sgd(-1, st["a_outs"], 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False))
+    del params, moms
     e, s, K = w.total_elems, w.elem_size, st["K"]
     res = {
         "workload": name, "elements": e, "buckets": st["nb"], "K": K,
@@ -143,6 +150,7 @@ def time_workload(name, steps, warmup, dev, in_place=True):
         "unpack_ms": ms_unpack, "unpack_GBps": 2 * s * e / (ms_unpack * 1e-3) / 1e9,
         "fused_ms": ms_fused, "fused_GBps": (K + 1) * s * e / (ms_fused * 1e-3) / 1e9,
         "fused_buckets_per_s": st["nb"] / (ms_fused * 1e-3),
+        "unpack_sgd_ms": ms_sgd, "unpack_sgd_GBps": (s + 16) * e / (ms_sgd * 1e-3) / 1e9,
     }
     return res, st
 

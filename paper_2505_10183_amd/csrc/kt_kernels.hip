@@ -716,6 +716,49 @@ __device__ __forceinline__ void sgd_elem(float x, float &p, float &v, const KtSg
     v = vn;
 }
 
+// four consecutive gradient elements
+template <typename T> struct Quad;
+template <> struct Quad<float> { u32x4 d; };
+template <> struct Quad<uint16_t> { uint32_t d[2]; };
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ Quad<float> ld_quad(const Quad<float> *p)
+{
+    Quad<float> q;
+    q.d = ld_vec(p);
+    return q;
+}
+__device__ __forceinline__ Quad<uint16_t> ld_quad(const Quad<uint16_t> *p)
+{
+    const u32x2 t = __builtin_nontemporal_load((const KT_GLOBAL u32x2 *)p);
+    Quad<uint16_t> q;
+    q.d[0] = t[0];
+    q.d[1] = t[1];
+    return q;
+}
+__device__ __forceinline__ void sgd_quad(const Quad<float> &g, u32x4 &p, u32x4 &v, const KtSgd &a)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float pp = __uint_as_float(p[c]), vv = __uint_as_float(v[c]);
+        sgd_elem(__uint_as_float(g.d[c]), pp, vv, a);
+        p[c] = __float_as_uint(pp);
+        v[c] = __float_as_uint(vv);
+    }
+}
+__device__ __forceinline__ void sgd_quad(const Quad<uint16_t> &g, u32x4 &p, u32x4 &v, const KtSgd &a)
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        float p0 = __uint_as_float(p[2 * c]), v0 = __uint_as_float(v[2 * c]);
+        float p1 = __uint_as_float(p[2 * c + 1]), v1 = __uint_as_float(v[2 * c + 1]);
+        sgd_elem(bf16_lo(g.d[c]), p0, v0, a);
+        sgd_elem(bf16_hi(g.d[c]), p1, v1, a);
+        p[2 * c] = __float_as_uint(p0); v[2 * c] = __float_as_uint(v0);
+        p[2 * c + 1] = __float_as_uint(p1); v[2 * c + 1] = __float_as_uint(v1);
+    }
+}
+
 // one 16-byte gradient vector against its 4 (fp32) or 8 (bf16) parameters
 template <typename T> struct SgdVec;
 template <> struct SgdVec<float> {
@@ -757,7 +800,6 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
     constexpr int VE = Elem<T>::VE;
     constexpr int PV = SgdVec<T>::PV;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
-    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
     __shared__ LdsTable2 lds;
 
     const KtTile tl = tb.tiles[tile0 + blockIdx.x];
@@ -766,54 +808,50 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
     const int tid = threadIdx.x;
 
     if (vec_ok && tl.nt == 0) {
+        // Solid tile, processed in quads of 4 elements so that every access is
+        // coalesced: 16 bytes of p and of v per lane, 16 (fp32) or 8 (bf16)
+        // bytes of gradient.
         const int64_t rel = g.start - tb.t_off[tl.t0];
         float *pp = reinterpret_cast<float *>(param_ptrs[tl.t0]) + rel;
         float *vp = reinterpret_cast<float *>(mom_ptrs[tl.t0]) + rel;
         if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0) {
-            const u32x4 *s4 = reinterpret_cast<const u32x4 *>(src + g.start);
+            constexpr int QPT = (int)(TILE_ELEMS / 4 / KT_BLOCK);     // quads per lane in a full tile
+            const Quad<T> *s4 = reinterpret_cast<const Quad<T> *>(src + g.start);
             u32x4 *p4 = reinterpret_cast<u32x4 *>(pp);
             u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
-            const int nvec = (int)((g.end - g.start) / VE);
-            if (nvec == KT_TILE_VECS) {
-                u32x4 gr[VPT], pr[VPT][PV], vr[VPT][PV];
+            const int nq = (int)((g.end - g.start) / 4);
+            if (nq == QPT * KT_BLOCK) {
+                constexpr int QB = 4;          // quads in flight per lane
+                static_assert(QPT % QB == 0, "quads per lane");
+#pragma unroll 1
+                for (int u0 = 0; u0 < QPT; u0 += QB) {
+                    Quad<T> gr[QB];
+                    u32x4 pr[QB], vr[QB];
 #pragma unroll
-                for (int u = 0; u < VPT; ++u) {
-                    const int idx = u * KT_BLOCK + tid;
-                    gr[u] = ld_vec(s4 + idx);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        pr[u][h] = ld_vec(p4 + idx * PV + h);
-                        vr[u][h] = u32x4{0, 0, 0, 0};
-                        if (!a.first) vr[u][h] = ld_vec(v4 + idx * PV + h);
+                    for (int u = 0; u < QB; ++u) {
+                        const int idx = (u0 + u) * KT_BLOCK + tid;
+                        gr[u] = ld_quad(s4 + idx);
+                        pr[u] = ld_vec(p4 + idx);
+                        vr[u] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[u] = ld_vec(v4 + idx);
                     }
-                }
 #pragma unroll
-                for (int u = 0; u < VPT; ++u) {
-                    const int idx = u * KT_BLOCK + tid;
-                    SgdVec<T>::apply(gr[u], pr[u], vr[u], a);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        st_vec(p4 + idx * PV + h, pr[u][h]);
-                        st_vec(v4 + idx * PV + h, vr[u][h]);
+                    for (int u = 0; u < QB; ++u) {
+                        const int idx = (u0 + u) * KT_BLOCK + tid;
+                        sgd_quad(gr[u], pr[u], vr[u], a);
+                        st_vec(p4 + idx, pr[u]);
+                        st_vec(v4 + idx, vr[u]);
                     }
                 }
             } else {
 #pragma unroll 1
-                for (int idx = tid; idx < nvec; idx += KT_BLOCK) {
-                    u32x4 pr[PV], vr[PV];
-                    const u32x4 gr = ld_vec(s4 + idx);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        pr[h] = ld_vec(p4 + idx * PV + h);
-                        vr[h] = u32x4{0, 0, 0, 0};
-                        if (!a.first) vr[h] = ld_vec(v4 + idx * PV + h);
-                    }
-                    SgdVec<T>::apply(gr, pr, vr, a);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        st_vec(p4 + idx * PV + h, pr[h]);
-                        st_vec(v4 + idx * PV + h, vr[h]);
-                    }
+                for (int idx = tid; idx < nq; idx += KT_BLOCK) {
+                    const Quad<T> gq = ld_quad(s4 + idx);
+                    u32x4 pr = ld_vec(p4 + idx), vr = u32x4{0, 0, 0, 0};
+                    if (!a.first) vr = ld_vec(v4 + idx);
+                    sgd_quad(gq, pr, vr, a);
+                    st_vec(p4 + idx, pr);
+                    st_vec(v4 + idx, vr);
                 }
             }
             return;
