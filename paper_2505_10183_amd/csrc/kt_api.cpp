@@ -44,6 +44,19 @@ static kt_status hip_fail(const char *what, hipError_t e)
     return e == hipErrorOutOfMemory ? KT_ENOMEM : KT_EHIP;
 }
 
+// No exception may cross the C boundary.
+#define KT_GUARD_BEGIN try {
+#define KT_GUARD_END(who)                                              \
+    }                                                                  \
+    catch (const std::bad_alloc &) {                                   \
+        kt_set_error("%s: out of host memory", who);                   \
+        return KT_ENOMEM;                                              \
+    }                                                                  \
+    catch (...) {                                                      \
+        kt_set_error("%s: unexpected internal error", who);            \
+        return KT_EINVAL;                                              \
+    }
+
 // ---- plan object -----------------------------------------------------------
 
 // A per-call table of device pointers (tensor/bucket or peer/out pointers)
@@ -55,15 +68,29 @@ struct PtrSlot {
     size_t cap = 0;               // capacity in entries
     size_t n = 0;                 // entries in use
     hipEvent_t uploaded = nullptr;
-    hipEvent_t last_use = nullptr;
     hipStream_t upload_stream = nullptr;
-    hipStream_t use_stream = nullptr;
+    hipStream_t use_stream = nullptr;   // stream of the last launch that read the table
+    uint64_t last_seq = 0;              // plan-wide sequence number of that launch
     bool multi_stream = false;
     bool valid = false;
     uint64_t stamp = 0;
 };
 
+// Before a table is overwritten, the launches that read it must have finished.
+// Recording an event after every launch would put a marker between all kernels;
+// instead every KT_TICK_EVERY-th launch records a "tick" event carrying the
+// launch sequence number, and a table may be overwritten once a tick that is
+// not older than its last use has completed (streams run in order).
+struct Tick {
+    hipEvent_t ev = nullptr;
+    hipStream_t stream = nullptr;
+    uint64_t seq = 0;
+    bool valid = false;
+};
+
 static const int KT_SLOTS = 8;
+static const int KT_TICKS = 16;
+static const uint64_t KT_TICK_EVERY = 4;
 
 struct kt_plan {
     KtHostPlan hp;
@@ -72,6 +99,9 @@ struct kt_plan {
     void *dev_blob = nullptr;
     KtDeviceTables tb{};
     PtrSlot slots[KT_SLOTS];
+    Tick ticks[KT_TICKS];
+    int tick_head = 0;
+    uint64_t seq = 0;      // launches issued through this plan
     uint64_t clock = 0;
 };
 
@@ -111,8 +141,9 @@ extern "C" kt_status kt_plan_destroy(kt_plan *p)
             if (s.dev) (void)hipFree(s.dev);
             if (s.pinned) (void)hipHostFree(s.pinned);
             if (s.uploaded) (void)hipEventDestroy(s.uploaded);
-            if (s.last_use) (void)hipEventDestroy(s.last_use);
         }
+        for (Tick &t : p->ticks)
+            if (t.ev) (void)hipEventDestroy(t.ev);
         if (p->dev_blob) (void)hipFree(p->dev_blob);
         if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
     }
@@ -215,11 +246,21 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
         if (!victim || s.stamp < victim->stamp) victim = &s;
     }
     if (victim->valid) {
-        // the last kernels that read this table must have finished
-        e = victim->multi_stream ? hipDeviceSynchronize() : hipEventSynchronize(victim->last_use);
+        // the upload and the launches that read this table must have finished
+        if (victim->last_seq == 0) {
+            e = hipEventSynchronize(victim->uploaded);
+        } else if (victim->multi_stream) {
+            e = hipDeviceSynchronize();
+        } else {
+            const Tick *best = nullptr;
+            for (const Tick &t : p->ticks)
+                if (t.valid && t.stream == victim->use_stream && t.seq >= victim->last_seq && (!best || t.seq < best->seq))
+                    best = &t;
+            e = best ? hipEventSynchronize(best->ev) : hipStreamSynchronize(victim->use_stream);
+        }
         if (e != hipSuccess) return hip_fail("waiting for a pointer table to retire", e);
-        victim->valid = false;
     }
+    victim->valid = false;
     if (victim->cap < n) {
         if (victim->dev) (void)hipFree(victim->dev);
         if (victim->pinned) (void)hipHostFree(victim->pinned);
@@ -234,8 +275,6 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
     if (!victim->uploaded) {
         e = hipEventCreateWithFlags(&victim->uploaded, hipEventDisableTiming);
         if (e != hipSuccess) return hip_fail("hipEventCreate", e);
-        e = hipEventCreateWithFlags(&victim->last_use, hipEventDisableTiming);
-        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
     }
     memcpy(victim->pinned, vals, n * 8);
     e = hipMemcpyAsync(victim->dev, victim->pinned, n * 8, hipMemcpyHostToDevice, stream);
@@ -245,6 +284,7 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
     victim->n = n;
     victim->upload_stream = stream;
     victim->use_stream = stream;
+    victim->last_seq = 0;
     victim->multi_stream = false;
     victim->valid = true;
     victim->stamp = ++p->clock;
@@ -252,12 +292,26 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
     return KT_OK;
 }
 
-static kt_status mark_used(PtrSlot *s, hipStream_t stream)
+// Bookkeeping after a launch that read `s` on `stream`.  Caller holds p->mu.
+static kt_status mark_used(kt_plan *p, PtrSlot *s, hipStream_t stream)
 {
-    if (s->use_stream != stream) s->multi_stream = true;
+    if (s->last_seq > 0 && s->use_stream != stream) s->multi_stream = true;
     s->use_stream = stream;
-    hipError_t e = hipEventRecord(s->last_use, stream);
-    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    s->last_seq = ++p->seq;
+    if (p->seq % KT_TICK_EVERY == 0) {
+        Tick &t = p->ticks[p->tick_head];
+        p->tick_head = (p->tick_head + 1) % KT_TICKS;
+        if (!t.ev) {
+            hipError_t e = hipEventCreateWithFlags(&t.ev, hipEventDisableTiming);
+            if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+        }
+        t.valid = false;
+        hipError_t e = hipEventRecord(t.ev, stream);
+        if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+        t.stream = stream;
+        t.seq = p->seq;
+        t.valid = true;
+    }
     return KT_OK;
 }
 
@@ -317,6 +371,7 @@ static kt_status prepare_tensor_call(kt_plan *p, int bucket, const void *const *
 extern "C" kt_status kt_bucket_pack(kt_plan *p, int bucket, const void *const *tensor_ptrs, void *const *bucket_bufs,
                                     void *stream)
 {
+    KT_GUARD_BEGIN
     if (!p) { kt_set_error("kt_bucket_pack: NULL plan"); return KT_EINVAL; }
     std::lock_guard<std::mutex> lock(p->mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -330,12 +385,14 @@ extern "C" kt_status kt_bucket_pack(kt_plan *p, int bucket, const void *const *t
     void *const *d_b = reinterpret_cast<void *const *>(static_cast<uint64_t *>(slot->dev) + T);
     int e = kt_launch_pack(p->tb, p->hp.dt, tile0, ntiles, d_t, d_b, vec, stream);
     if (e != 0) return hip_fail("kt_bucket_pack: launch", (hipError_t)e);
-    return mark_used(slot, s);
+    return mark_used(p, slot, s);
+    KT_GUARD_END("kt_bucket_pack")
 }
 
 extern "C" kt_status kt_bucket_unpack_scale(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
                                             void *const *tensor_ptrs, void *stream)
 {
+    KT_GUARD_BEGIN
     if (!p) { kt_set_error("kt_bucket_unpack_scale: NULL plan"); return KT_EINVAL; }
     std::lock_guard<std::mutex> lock(p->mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -349,12 +406,14 @@ extern "C" kt_status kt_bucket_unpack_scale(kt_plan *p, int bucket, const void *
     const void *const *d_b = reinterpret_cast<const void *const *>(static_cast<uint64_t *>(slot->dev) + T);
     int e = kt_launch_unpack(p->tb, p->hp.dt, tile0, ntiles, d_b, scale, d_t, vec, stream);
     if (e != 0) return hip_fail("kt_bucket_unpack_scale: launch", (hipError_t)e);
-    return mark_used(slot, s);
+    return mark_used(p, slot, s);
+    KT_GUARD_END("kt_bucket_unpack_scale")
 }
 
 extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *const *peer_bufs, int K,
                                         const float *weights, void *const *out_bufs, void *stream)
 {
+    KT_GUARD_BEGIN
     const char *who = "kt_weighted_reduce";
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
@@ -403,13 +462,15 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     void *const *d_o = reinterpret_cast<void *const *>(static_cast<uint64_t *>(slot->dev) + nb * K);
     int e = kt_launch_reduce(p->tb, hp.dt, tile0, ntiles, d_p, K, w, d_o, vec, stream);
     if (e != 0) return hip_fail("kt_weighted_reduce: launch", (hipError_t)e);
-    return mark_used(slot, s);
+    return mark_used(p, slot, s);
+    KT_GUARD_END("kt_weighted_reduce")
 }
 
 extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
                                    const void *const *peer_bufs, int K, const float *weights, float scale,
                                    void *const *out_tensor_ptrs, void *stream)
 {
+    KT_GUARD_BEGIN
     const char *who = "kt_fused_step";
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
@@ -466,13 +527,15 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
                             reinterpret_cast<const void *const *>(d + 2 * T), K, w, scale,
                             reinterpret_cast<void *const *>(const_cast<uint64_t *>(d + T)), vec, stream);
     if (e != 0) return hip_fail("kt_fused_step: launch", (hipError_t)e);
-    return mark_used(slot, s);
+    return mark_used(p, slot, s);
+    KT_GUARD_END("kt_fused_step")
 }
 
 extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
                                           void *const *param_ptrs, void *const *momentum_ptrs, float lr,
                                           float momentum, float weight_decay, int first_step, void *stream)
 {
+    KT_GUARD_BEGIN
     const char *who = "kt_bucket_unpack_sgd";
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     std::lock_guard<std::mutex> lock(p->mu);
@@ -518,5 +581,6 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
                                  reinterpret_cast<void *const *>(d), reinterpret_cast<void *const *>(d + T), a, vec,
                                  stream);
     if (e != 0) return hip_fail("kt_bucket_unpack_sgd: launch", (hipError_t)e);
-    return mark_used(slot, s);
+    return mark_used(p, slot, s);
+    KT_GUARD_END("kt_bucket_unpack_sgd")
 }

@@ -515,3 +515,39 @@ def test_two_level_reduce_with_pinned_host_inputs(dtype):
         if dtype == "f32":   # and it agrees with the flat combination within the fp32 bound
             gmax = max(float(np.abs(x).max()) for x in hp)
             assert_close(got, oracle.weighted_reduce(hp, flat, dtype, "D"), dtype, gmax, "flat, bucket %d" % b)
+
+
+def test_pointer_churn_and_streams():
+    """More distinct pointer sets than the library keeps resident (tables are
+    evicted and re-uploaded while earlier launches may still run), on two
+    streams, with results checked for every call."""
+    w = wl.ragged_workload(dtype="f32", K=2, seed=55, n_tensors=30)
+    plan = kt.Plan(w.numels, "f32", w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    wts = np.array([0.75, 0.25], np.float32)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    rounds = []
+    for r in range(40):
+        st = streams[r % 2]
+        with torch.cuda.stream(st):
+            peers = [[wl.flat_normal(n, "f32", 1e-3, 5000 + 100 * r + 10 * k + b, DEV)
+                      for b, n in enumerate(plan.bucket_elems())] for k in range(2)]
+            outs = [torch.empty_like(peers[0][b]) for b in range(nb)]
+            plan.kt_weighted_reduce(-1, [peers[k][b] for b in range(nb) for k in range(2)], 2, list(wts), outs, stream=st)
+        rounds.append((peers, outs))
+    torch.cuda.synchronize()
+    for r, (peers, outs) in enumerate(rounds):
+        for b in (0, nb - 1):
+            want = oracle.weighted_reduce([host(peers[k][b]) for k in range(2)], wts, "f32", "S")
+            assert raw(host(outs[b])).tobytes() == raw(want).tobytes(), (r, b)
+    # the same table used from two streams, then evicted
+    peers, outs = rounds[-1]
+    flat = [peers[k][b] for b in range(nb) for k in range(2)]
+    for st in streams:
+        plan.kt_weighted_reduce(-1, flat, 2, list(wts), outs, stream=st)
+    for r in range(10):
+        p2 = [[torch.full_like(t, float(r)) for t in pk] for pk in peers]
+        o2 = [torch.empty_like(t) for t in outs]
+        plan.kt_weighted_reduce(-1, [p2[k][b] for b in range(nb) for k in range(2)], 2, list(wts), o2)
+        torch.cuda.synchronize()
+        assert all(bool((t == float(r)).all()) for t in o2)
