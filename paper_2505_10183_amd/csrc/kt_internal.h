@@ -16,7 +16,9 @@
 #define KT_BLOCK 256
 // Mixed tiles holding at most this many tensors stage their slice of the
 // tensor table in LDS; larger ones search the table in global memory.
+#ifndef KT_LDS_TENSORS
 #define KT_LDS_TENSORS 512
+#endif
 
 // Per-tile record (device table).  `nt == 0` marks a solid tile: tensor `t0`
 // covers every element of the tile and the tile is a whole number of 16-byte

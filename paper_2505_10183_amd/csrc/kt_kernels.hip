@@ -128,34 +128,137 @@ __device__ __forceinline__ TileGeom tile_geom(const KtTile &tl, const int64_t *b
     return g;
 }
 
-// Stage the tile's slice of the tensor table in LDS when it fits, so that the
-// per-vector owner search runs on LDS instead of global memory.
+// The tile's slice of the tensor table is staged in LDS when it fits, so that
+// the per-vector owner search runs on LDS instead of global memory.
 struct LdsTable {
     int64_t off[KT_LDS_TENSORS];
     int64_t numel[KT_LDS_TENSORS];
     uintptr_t ptr[KT_LDS_TENSORS];
 };
 
-__device__ __forceinline__ TableView stage_table(LdsTable &lds, const KtDeviceTables &tb,
-                                                 const void *const *tensor_ptrs, int t0, int nt)
+// Typed views of the table slice of a mixed tile: in LDS (the usual case) or in
+// global memory (more than KT_LDS_TENSORS tensors in one tile).  Keeping the
+// address space in the type lets the owner search use LDS instructions.
+#define KT_LDS __attribute__((address_space(3)))
+struct LdsView {
+    const KT_LDS int64_t *off;
+    const KT_LDS int64_t *numel;
+    const KT_LDS uintptr_t *ptr;
+};
+struct GlobalView {
+    const KT_GLOBAL int64_t *off;
+    const KT_GLOBAL int64_t *numel;
+    const KT_GLOBAL uintptr_t *ptr;
+};
+
+template <typename V> __device__ __forceinline__ int find_owner_v(const V &tv, int nt, int64_t e)
 {
-    TableView tv;
-    if (nt <= KT_LDS_TENSORS) {
-        for (int i = threadIdx.x; i < nt; i += KT_BLOCK) {
-            lds.off[i] = tb.t_off[t0 + i];
-            lds.numel[i] = tb.t_numel[t0 + i];
-            lds.ptr[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[t0 + i]);
-        }
-        __syncthreads();
-        tv.off = lds.off; tv.numel = lds.numel; tv.ptr = lds.ptr;
-    } else {
-        tv.off = tb.t_off + t0; tv.numel = tb.t_numel + t0;
-        tv.ptr = reinterpret_cast<const uintptr_t *>(tensor_ptrs) + t0;
+    int lo = 0, hi = nt;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (tv.off[mid] <= e) lo = mid + 1; else hi = mid;
     }
-    return tv;
+    return lo - 1;
+}
+
+__device__ __forceinline__ LdsView stage_lds(LdsTable &lds, const KtDeviceTables &tb, const void *const *tensor_ptrs,
+                                             int t0, int nt)
+{
+    for (int i = threadIdx.x; i < nt; i += KT_BLOCK) {
+        lds.off[i] = tb.t_off[t0 + i];
+        lds.numel[i] = tb.t_numel[t0 + i];
+        lds.ptr[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[t0 + i]);
+    }
+    __syncthreads();
+    LdsView v;
+    v.off = (const KT_LDS int64_t *)lds.off;
+    v.numel = (const KT_LDS int64_t *)lds.numel;
+    v.ptr = (const KT_LDS uintptr_t *)lds.ptr;
+    return v;
+}
+
+__device__ __forceinline__ GlobalView global_view(const KtDeviceTables &tb, const void *const *tensor_ptrs, int t0)
+{
+    GlobalView v;
+    v.off = (const KT_GLOBAL int64_t *)(tb.t_off + t0);
+    v.numel = (const KT_GLOBAL int64_t *)(tb.t_numel + t0);
+    v.ptr = (const KT_GLOBAL uintptr_t *)(reinterpret_cast<const uintptr_t *>(tensor_ptrs) + t0);
+    return v;
 }
 
 // ---- pack ----------------------------------------------------------------
+
+// One vector of a mixed tile, element by element: tensor tails, padding,
+// misaligned sources, vectors straddling tensors, the last partial vector of a
+// densely packed bucket.
+template <typename T, typename V>
+__device__ __forceinline__ void pack_slow(const V &tv, int nt, int64_t e0, int64_t b_n, T *dst)
+{
+    constexpr int VE = Elem<T>::VE;
+    int i = find_owner_v(tv, nt, e0);
+#pragma unroll 1
+    for (int q = 0; q < VE; ++q) {
+        const int64_t e = e0 + q;
+        if (e >= b_n) break;
+        while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+        T x = 0;
+        if (i >= 0 && e - tv.off[i] < tv.numel[i])
+            x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
+        st_elem(dst + e, x);
+    }
+}
+
+// Mixed tile, 16-byte path.  Two phases so that the loads of all of a lane's
+// vectors are in flight together: (1) find each vector's owner in the staged
+// table and issue its load, (2) store; stragglers go element by element.
+template <typename T, typename V>
+__device__ __forceinline__ void pack_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, T *dst)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+    u32x4 val[VPT];
+    int how[VPT];      // 0 = nothing, 1 = whole vector loaded, 2 = element-wise
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int v = j * KT_BLOCK + threadIdx.x;
+        how[j] = 0;
+        if (v < nvec) {
+            const int64_t e0 = g.start + (int64_t)v * VE;
+            how[j] = 2;
+            const int i = find_owner_v(tv, nt, e0);
+            if (i >= 0 && e0 + VE <= b_n) {
+                const int64_t r = e0 - tv.off[i];
+                if (r + VE <= tv.numel[i]) {
+                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                    if ((p & 15u) == 0) {
+                        val[j] = ld_vec(reinterpret_cast<const void *>(p));
+                        how[j] = 1;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int64_t e0 = g.start + (int64_t)(j * KT_BLOCK + threadIdx.x) * VE;
+        if (how[j] == 1) st_vec(dst + e0, val[j]);
+        else if (how[j] == 2) pack_slow<T>(tv, nt, e0, b_n, dst);
+    }
+}
+
+// Any alignment: one element per lane per step, coalesced.
+template <typename T, typename V>
+__device__ __forceinline__ void pack_elems(const V &tv, int nt, const TileGeom &g, T *dst)
+{
+    for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
+        const int i = find_owner_v(tv, nt, e);
+        T x = 0;
+        if (i >= 0 && e - tv.off[i] < tv.numel[i])
+            x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
+        st_elem(dst + e, x);
+    }
+}
 
 template <typename T, bool VEC>
 __global__ __launch_bounds__(KT_BLOCK) void kt_pack_kernel(KtDeviceTables tb, int64_t tile0,
@@ -195,57 +298,79 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_pack_kernel(KtDeviceTables tb, in
     }
 
     const int nt = tl.nt == 0 ? 1 : tl.nt;
-    const TableView tv = stage_table(lds, tb, tensor_ptrs, tl.t0, nt);
-
-    if (VEC) {
-        const int64_t b_n = tb.b_elems[g.bucket];
-        const int nvec = (int)((g.end - g.start + VE - 1) / VE);
-#pragma unroll 1
-        for (int v = tid; v < nvec; v += KT_BLOCK) {
-            const int64_t e0 = g.start + (int64_t)v * VE;
-            int i = find_owner(tv, nt, e0);
-            bool whole = false;
-            u32x4 val;
-            if (i >= 0) {
-                const int64_t r = e0 - tv.off[i];
-                if (r + VE <= tv.numel[i]) {
-                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
-                    if ((p & 15u) == 0) {
-                        val = ld_vec(reinterpret_cast<const void *>(p));
-                        whole = true;
-                    }
-                }
-            }
-            if (whole && e0 + VE <= b_n) {
-                st_vec(dst + e0, val);
-                continue;
-            }
-            // element-wise: tensor tails, padding, misaligned sources, and the
-            // last partial vector of a densely packed bucket
-#pragma unroll 1
-            for (int q = 0; q < VE; ++q) {
-                const int64_t e = e0 + q;
-                if (e >= b_n) break;
-                while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
-                T x = 0;
-                if (i >= 0 && e - tv.off[i] < tv.numel[i])
-                    x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
-                st_elem(dst + e, x);
-            }
-        }
+    const int64_t b_n = tb.b_elems[g.bucket];
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, tensor_ptrs, tl.t0, nt);
+        if (VEC) pack_mixed<T>(tv, nt, g, b_n, dst); else pack_elems<T>(tv, nt, g, dst);
     } else {
-        // any alignment: one element per lane per step, coalesced
-        for (int64_t e = g.start + tid; e < g.end; e += KT_BLOCK) {
-            const int i = find_owner(tv, nt, e);
-            T x = 0;
-            if (i >= 0 && e - tv.off[i] < tv.numel[i])
-                x = ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + (e - tv.off[i]));
-            st_elem(dst + e, x);
-        }
+        const GlobalView tv = global_view(tb, tensor_ptrs, tl.t0);
+        if (VEC) pack_mixed<T>(tv, nt, g, b_n, dst); else pack_elems<T>(tv, nt, g, dst);
     }
 }
 
 // ---- unpack with scale ----------------------------------------------------
+
+template <typename T, typename V>
+__device__ __forceinline__ void unpack_slow(const V &tv, int nt, int64_t e0, int64_t b_n, const T *src, float scale)
+{
+    constexpr int VE = Elem<T>::VE;
+    int i = find_owner_v(tv, nt, e0);
+#pragma unroll 1
+    for (int q = 0; q < VE; ++q) {
+        const int64_t e = e0 + q;
+        if (e >= b_n) break;
+        while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+        if (i >= 0 && e - tv.off[i] < tv.numel[i])
+            st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
+    }
+}
+
+template <typename T, typename V>
+__device__ __forceinline__ void unpack_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, const T *src,
+                                             float scale)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+    u32x4 val[VPT];
+    uintptr_t where[VPT];   // destination of a whole vector, 0 = none, 1 = element-wise
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        const int v = j * KT_BLOCK + threadIdx.x;
+        where[j] = 0;
+        if (v < nvec) {
+            const int64_t e0 = g.start + (int64_t)v * VE;
+            where[j] = 1;
+            const int i = find_owner_v(tv, nt, e0);
+            if (i >= 0 && e0 + VE <= b_n) {
+                const int64_t r = e0 - tv.off[i];
+                if (r + VE <= tv.numel[i]) {
+                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                    if ((p & 15u) == 0) {
+                        val[j] = ld_vec(src + e0);
+                        where[j] = p;
+                    }
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < VPT; ++j) {
+        if (where[j] > 1) st_vec(reinterpret_cast<void *>(where[j]), scale_vec<T>(val[j], scale));
+        else if (where[j] == 1)
+            unpack_slow<T>(tv, nt, g.start + (int64_t)(j * KT_BLOCK + threadIdx.x) * VE, b_n, src, scale);
+    }
+}
+
+template <typename T, typename V>
+__device__ __forceinline__ void unpack_elems(const V &tv, int nt, const TileGeom &g, const T *src, float scale)
+{
+    for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
+        const int i = find_owner_v(tv, nt, e);
+        if (i >= 0 && e - tv.off[i] < tv.numel[i])
+            st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
+    }
+}
 
 template <typename T, bool VEC>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_kernel(KtDeviceTables tb, int64_t tile0,
@@ -283,41 +408,14 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_kernel(KtDeviceTables tb, 
     }
 
     const int nt = tl.nt == 0 ? 1 : tl.nt;
-    const TableView tv = stage_table(lds, tb, reinterpret_cast<const void *const *>(tensor_ptrs), tl.t0, nt);
-
-    if (VEC) {
-        const int64_t b_n = tb.b_elems[g.bucket];
-        const int nvec = (int)((g.end - g.start + VE - 1) / VE);
-#pragma unroll 1
-        for (int v = tid; v < nvec; v += KT_BLOCK) {
-            const int64_t e0 = g.start + (int64_t)v * VE;
-            int i = find_owner(tv, nt, e0);
-            const bool in_bucket = e0 + VE <= b_n;
-            if (in_bucket && i >= 0) {
-                const int64_t r = e0 - tv.off[i];
-                if (r + VE <= tv.numel[i]) {
-                    const uintptr_t p = tv.ptr[i] + (uintptr_t)r * sizeof(T);
-                    if ((p & 15u) == 0) {
-                        st_vec(reinterpret_cast<void *>(p), scale_vec<T>(ld_vec(src + e0), scale));
-                        continue;
-                    }
-                }
-            }
-#pragma unroll 1
-            for (int q = 0; q < VE; ++q) {
-                const int64_t e = e0 + q;
-                if (e >= b_n) break;
-                while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
-                if (i >= 0 && e - tv.off[i] < tv.numel[i])
-                    st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
-            }
-        }
+    const int64_t b_n = tb.b_elems[g.bucket];
+    const void *const *tp = reinterpret_cast<const void *const *>(tensor_ptrs);
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, tp, tl.t0, nt);
+        if (VEC) unpack_mixed<T>(tv, nt, g, b_n, src, scale); else unpack_elems<T>(tv, nt, g, src, scale);
     } else {
-        for (int64_t e = g.start + tid; e < g.end; e += KT_BLOCK) {
-            const int i = find_owner(tv, nt, e);
-            if (i >= 0 && e - tv.off[i] < tv.numel[i])
-                st_elem(reinterpret_cast<T *>(tv.ptr[i]) + (e - tv.off[i]), scale_elem(ld_elem(src + e), scale));
-        }
+        const GlobalView tv = global_view(tb, tp, tl.t0);
+        if (VEC) unpack_mixed<T>(tv, nt, g, b_n, src, scale); else unpack_elems<T>(tv, nt, g, src, scale);
     }
 }
 

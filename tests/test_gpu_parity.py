@@ -551,3 +551,70 @@ def test_pointer_churn_and_streams():
         plan.kt_weighted_reduce(-1, [p2[k][b] for b in range(nb) for k in range(2)], 2, list(wts), o2)
         torch.cuda.synchronize()
         assert all(bool((t == float(r)).all()) for t in o2)
+
+
+def test_edge_shapes():
+    """Zero-size tensors, a one-element plan, a bucket of exactly one tile, the
+    maximum peer count, and an empty plan."""
+    # zero-size tensors between real ones (their pointers may be NULL)
+    numels = [0, 5, 0, 0, 4096, 0, 3, 0]
+    plan = kt.Plan(numels, "f32", 0, 16)
+    L = oracle.assign_buckets(numels, 4, 0, 16)
+    assert [plan.tensor_info(t) for t in range(8)] == list(zip(L["tensor_bucket"], L["tensor_offset"]))
+    tensors = [torch.randn(n, device=DEV) if n else None for n in numels]
+    bufs = alloc_buckets(plan, "f32", fill=0x33333333)
+    plan.kt_bucket_pack(-1, tensors, bufs)
+    torch.cuda.synchronize()
+    want = oracle.pack(L, [host(t) if t is not None else np.zeros(0, np.float32) for t in tensors], "f32")
+    assert raw(host(bufs[0])).tobytes() == raw(want[0]).tobytes()
+    outs = [torch.zeros(n, device=DEV) if n else None for n in numels]
+    plan.kt_bucket_unpack_scale(-1, bufs, 2.0, outs)
+    plan.kt_fused_step(-1, tensors, [], 1, [1.0], 2.0, [torch.zeros(n, device=DEV) if n else None for n in numels])
+    torch.cuda.synchronize()
+    for t, o in zip(tensors, outs):
+        if t is not None:
+            assert torch.equal(o, t * 2.0)
+    # one element
+    p1 = kt.Plan([1], "bf16", 0, 16)
+    assert p1.bucket_elems() == [8]
+    x = torch.tensor([1.5], dtype=torch.bfloat16, device=DEV)
+    b1 = alloc_buckets(p1, "bf16", fill=0x4444)
+    p1.kt_bucket_pack(0, [x], b1)
+    o1 = [torch.empty(8, dtype=torch.bfloat16, device=DEV)]
+    p1.kt_weighted_reduce(0, [b1[0], b1[0]], 2, [0.5, 0.25], o1)
+    r1 = [torch.zeros(1, dtype=torch.bfloat16, device=DEV)]
+    p1.kt_bucket_unpack_scale(0, o1, 2.0, r1)
+    torch.cuda.synchronize()
+    assert float(b1[0][0]) == 1.5 and bool((b1[0][1:] == 0).all()) and float(r1[0][0]) == 2.25
+    # exactly one full tile, then one element more
+    for n in (4096, 4097):
+        pt = kt.Plan([n], "f32", 0, 16)
+        assert pt.num_tiles == (1 if n == 4096 else 2)
+        xs = [torch.randn(pt.bucket_elems()[0], device=DEV) for _ in range(3)]
+        o = [torch.empty_like(xs[0])]
+        pt.kt_weighted_reduce(-1, xs, 3, [0.5, 0.25, 0.25], o)
+        torch.cuda.synchronize()
+        wantS = oracle.weighted_reduce([host(t) for t in xs], np.array([0.5, 0.25, 0.25], np.float32), "f32", "S")
+        assert raw(host(o[0])).tobytes() == raw(wantS).tobytes()
+    # the maximum number of peers
+    K = kt.binding.KT_MAX_PEERS
+    pk = kt.Plan([5000, 3], "bf16", 0, 16)
+    n = pk.bucket_elems()[0]
+    xs = [wl.flat_normal(n, "bf16", 1e-3, 40 + k, DEV) for k in range(K)]
+    wts = np.full(K, 1.0 / K, np.float32)
+    o = [torch.empty_like(xs[0])]
+    pk.kt_weighted_reduce(-1, xs, K, list(wts), o)
+    loc = [xs[0][:5000].clone(), xs[0][5000:5003].clone()]
+    res = [torch.empty_like(t) for t in loc]
+    pk.kt_fused_step(-1, loc, xs[1:], K, list(wts), 1.0, res)
+    torch.cuda.synchronize()
+    wantS = oracle.weighted_reduce([host(t) for t in xs], wts, "bf16", "S")
+    assert host(o[0]).tobytes() == wantS.tobytes()
+    assert host(res[0]).tobytes() == wantS[:5000].tobytes() and host(res[1]).tobytes() == wantS[5000:5003].tobytes()
+    # nothing to do
+    pe = kt.Plan([], "f32", 0, 16)
+    pe.kt_bucket_pack(-1, [], [])
+    pz = kt.Plan([0, 0], "f32", 0, 16)
+    assert pz.num_buckets == 1 and pz.bucket_elems() == [0] and pz.num_tiles == 0
+    pz.kt_bucket_pack(-1, [None, None], [None])
+    pz.kt_weighted_reduce(-1, [None], 1, [1.0], [None])
