@@ -91,27 +91,6 @@ template <> __device__ __forceinline__ u32x4 scale_vec<uint16_t>(u32x4 v, float 
     return r;
 }
 
-// ---- tensor-table views for mixed tiles ---------------------------------
-// A view exposes, for local index i in [0, nt): the tensor's element offset in
-// the bucket, its element count and its base address.
-
-struct TableView {
-    const int64_t *off;
-    const int64_t *numel;
-    const uintptr_t *ptr;
-};
-
-// last i in [0, nt) with off[i] <= e, or -1
-__device__ __forceinline__ int find_owner(const TableView &tv, int nt, int64_t e)
-{
-    int lo = 0, hi = nt;
-    while (lo < hi) {
-        int mid = (lo + hi) >> 1;
-        if (tv.off[mid] <= e) lo = mid + 1; else hi = mid;
-    }
-    return lo - 1;
-}
-
 struct TileGeom {
     int bucket;
     int64_t start;   // first element of the tile inside the bucket
@@ -131,9 +110,10 @@ __device__ __forceinline__ TileGeom tile_geom(const KtTile &tl, const int64_t *b
 // The tile's slice of the tensor table is staged in LDS when it fits, so that
 // the per-vector owner search runs on LDS instead of global memory.
 struct LdsTable {
-    int64_t off[KT_LDS_TENSORS];
-    int64_t numel[KT_LDS_TENSORS];
-    uintptr_t ptr[KT_LDS_TENSORS];
+    int64_t off[KT_LDS_TENSORS];     // element offset of the tensor in its bucket
+    int64_t numel[KT_LDS_TENSORS];   // element count
+    uintptr_t ptr[KT_LDS_TENSORS];   // base address (source or destination tensor)
+    uintptr_t ptr2[KT_LDS_TENSORS];  // second base address for kernels with two tensor sets
 };
 
 // Typed views of the table slice of a mixed tile: in LDS (the usual case) or in
@@ -144,11 +124,13 @@ struct LdsView {
     const KT_LDS int64_t *off;
     const KT_LDS int64_t *numel;
     const KT_LDS uintptr_t *ptr;
+    const KT_LDS uintptr_t *ptr2;
 };
 struct GlobalView {
     const KT_GLOBAL int64_t *off;
     const KT_GLOBAL int64_t *numel;
     const KT_GLOBAL uintptr_t *ptr;
+    const KT_GLOBAL uintptr_t *ptr2;
 };
 
 template <typename V> __device__ __forceinline__ int find_owner_v(const V &tv, int nt, int64_t e)
@@ -161,28 +143,33 @@ template <typename V> __device__ __forceinline__ int find_owner_v(const V &tv, i
     return lo - 1;
 }
 
-__device__ __forceinline__ LdsView stage_lds(LdsTable &lds, const KtDeviceTables &tb, const void *const *tensor_ptrs,
-                                             int t0, int nt)
+// `second` may be NULL for kernels with one tensor set (ptr2 then mirrors ptr).
+__device__ __forceinline__ LdsView stage_lds(LdsTable &lds, const KtDeviceTables &tb, const void *const *first,
+                                             const void *const *second, int t0, int nt)
 {
     for (int i = threadIdx.x; i < nt; i += KT_BLOCK) {
         lds.off[i] = tb.t_off[t0 + i];
         lds.numel[i] = tb.t_numel[t0 + i];
-        lds.ptr[i] = reinterpret_cast<uintptr_t>(tensor_ptrs[t0 + i]);
+        lds.ptr[i] = reinterpret_cast<uintptr_t>(first[t0 + i]);
+        lds.ptr2[i] = reinterpret_cast<uintptr_t>(second ? second[t0 + i] : first[t0 + i]);
     }
     __syncthreads();
     LdsView v;
     v.off = (const KT_LDS int64_t *)lds.off;
     v.numel = (const KT_LDS int64_t *)lds.numel;
     v.ptr = (const KT_LDS uintptr_t *)lds.ptr;
+    v.ptr2 = (const KT_LDS uintptr_t *)lds.ptr2;
     return v;
 }
 
-__device__ __forceinline__ GlobalView global_view(const KtDeviceTables &tb, const void *const *tensor_ptrs, int t0)
+__device__ __forceinline__ GlobalView global_view(const KtDeviceTables &tb, const void *const *first,
+                                                  const void *const *second, int t0)
 {
     GlobalView v;
     v.off = (const KT_GLOBAL int64_t *)(tb.t_off + t0);
     v.numel = (const KT_GLOBAL int64_t *)(tb.t_numel + t0);
-    v.ptr = (const KT_GLOBAL uintptr_t *)(reinterpret_cast<const uintptr_t *>(tensor_ptrs) + t0);
+    v.ptr = (const KT_GLOBAL uintptr_t *)(reinterpret_cast<const uintptr_t *>(first) + t0);
+    v.ptr2 = (const KT_GLOBAL uintptr_t *)(reinterpret_cast<const uintptr_t *>(second ? second : first) + t0);
     return v;
 }
 
@@ -300,10 +287,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_pack_kernel(KtDeviceTables tb, in
     const int nt = tl.nt == 0 ? 1 : tl.nt;
     const int64_t b_n = tb.b_elems[g.bucket];
     if (nt <= KT_LDS_TENSORS) {
-        const LdsView tv = stage_lds(lds, tb, tensor_ptrs, tl.t0, nt);
+        const LdsView tv = stage_lds(lds, tb, tensor_ptrs, nullptr, tl.t0, nt);
         if (VEC) pack_mixed<T>(tv, nt, g, b_n, dst); else pack_elems<T>(tv, nt, g, dst);
     } else {
-        const GlobalView tv = global_view(tb, tensor_ptrs, tl.t0);
+        const GlobalView tv = global_view(tb, tensor_ptrs, nullptr, tl.t0);
         if (VEC) pack_mixed<T>(tv, nt, g, b_n, dst); else pack_elems<T>(tv, nt, g, dst);
     }
 }
@@ -411,10 +398,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_kernel(KtDeviceTables tb, 
     const int64_t b_n = tb.b_elems[g.bucket];
     const void *const *tp = reinterpret_cast<const void *const *>(tensor_ptrs);
     if (nt <= KT_LDS_TENSORS) {
-        const LdsView tv = stage_lds(lds, tb, tp, tl.t0, nt);
+        const LdsView tv = stage_lds(lds, tb, tp, nullptr, tl.t0, nt);
         if (VEC) unpack_mixed<T>(tv, nt, g, b_n, src, scale); else unpack_elems<T>(tv, nt, g, src, scale);
     } else {
-        const GlobalView tv = global_view(tb, tp, tl.t0);
+        const GlobalView tv = global_view(tb, tp, nullptr, tl.t0);
         if (VEC) unpack_mixed<T>(tv, nt, g, b_n, src, scale); else unpack_elems<T>(tv, nt, g, src, scale);
     }
 }
@@ -622,12 +609,49 @@ hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntil
 // type, then one multiplication), so the results are bit-identical to the
 // chained path while moving (K+1) instead of (K+5) element sizes per element.
 
-struct LdsTable2 {
-    int64_t off[KT_LDS_TENSORS];
-    int64_t numel[KT_LDS_TENSORS];
-    uintptr_t src[KT_LDS_TENSORS];
-    uintptr_t dst[KT_LDS_TENSORS];
-};
+// Mixed tile of the fused pass: per vector, peer 0 comes from the owning tensor
+// (tv.ptr = local gradients), the result goes to the same position of tv.ptr2.
+template <typename T, int K, typename V>
+__device__ __forceinline__ void fused_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n,
+                                            const T *const *x, const float *w, float scale)
+{
+    constexpr int VE = Elem<T>::VE;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+        const int64_t e0 = g.start + (int64_t)v * VE;
+        int i = find_owner_v(tv, nt, e0);
+        if (i >= 0 && e0 + VE <= b_n) {
+            const int64_t r = e0 - tv.off[i];
+            if (r + VE <= tv.numel[i]) {
+                const uintptr_t ps = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                const uintptr_t pd = tv.ptr2[i] + (uintptr_t)r * sizeof(T);
+                if (((ps | pd) & 15u) == 0) {
+                    Acc<T> acc;
+                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), w[0]);
+#pragma unroll
+                    for (int k = 1; k < K; ++k)
+                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v), w[k]);
+                    st_vec(reinterpret_cast<void *>(pd), scale_vec<T>(acc.finish(), scale));
+                    continue;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int q = 0; q < VE; ++q) {
+            const int64_t e = e0 + q;
+            if (e >= b_n) break;
+            while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+            if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
+                const int64_t r = e - tv.off[i];
+                float a = __fmul_rn(w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
+#pragma unroll
+                for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k - 1] + (e - g.start))), a);
+                st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
+            }
+        }
+    }
+}
 
 template <typename T, int K>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, int64_t tile0,
@@ -639,7 +663,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
     constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
     constexpr int KP = K > 1 ? K - 1 : 1;
-    __shared__ LdsTable2 lds;
+    __shared__ LdsTable lds;
 
     const KtTile tl = tb.tiles[tile0 + blockIdx.x];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
@@ -692,62 +716,14 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
 
     // mixed tile: stage (offset, size, source, destination) of its tensors in LDS
     const int nt = tl.nt == 0 ? 1 : tl.nt;
-    const int64_t *t_off;
-    const int64_t *t_numel;
-    const uintptr_t *t_src;
-    const uintptr_t *t_dst;
-    if (nt <= KT_LDS_TENSORS) {
-        for (int i = tid; i < nt; i += KT_BLOCK) {
-            lds.off[i] = tb.t_off[tl.t0 + i];
-            lds.numel[i] = tb.t_numel[tl.t0 + i];
-            lds.src[i] = reinterpret_cast<uintptr_t>(local_ptrs[tl.t0 + i]);
-            lds.dst[i] = reinterpret_cast<uintptr_t>(out_ptrs[tl.t0 + i]);
-        }
-        __syncthreads();
-        t_off = lds.off; t_numel = lds.numel; t_src = lds.src; t_dst = lds.dst;
-    } else {
-        t_off = tb.t_off + tl.t0; t_numel = tb.t_numel + tl.t0;
-        t_src = reinterpret_cast<const uintptr_t *>(local_ptrs) + tl.t0;
-        t_dst = reinterpret_cast<const uintptr_t *>(out_ptrs) + tl.t0;
-    }
-    TableView tv;
-    tv.off = t_off; tv.numel = t_numel; tv.ptr = t_src;
-
     const int64_t b_n = tb.b_elems[g.bucket];
-    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
-#pragma unroll 1
-    for (int v = tid; v < nvec; v += KT_BLOCK) {
-        const int64_t e0 = g.start + (int64_t)v * VE;
-        int i = find_owner(tv, nt, e0);
-        if (i >= 0 && e0 + VE <= b_n) {
-            const int64_t r = e0 - t_off[i];
-            if (r + VE <= t_numel[i]) {
-                const uintptr_t ps = t_src[i] + (uintptr_t)r * sizeof(T);
-                const uintptr_t pd = t_dst[i] + (uintptr_t)r * sizeof(T);
-                if (((ps | pd) & 15u) == 0) {
-                    Acc<T> acc;
-                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), w[0]);
-#pragma unroll
-                    for (int k = 1; k < K; ++k)
-                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v), w[k]);
-                    st_vec(reinterpret_cast<void *>(pd), scale_vec<T>(acc.finish(), scale));
-                    continue;
-                }
-            }
-        }
-#pragma unroll 1
-        for (int q = 0; q < VE; ++q) {
-            const int64_t e = e0 + q;
-            if (e >= b_n) break;
-            while (i + 1 < nt && t_off[i + 1] <= e) ++i;
-            if (i >= 0 && e - t_off[i] < t_numel[i]) {
-                const int64_t r = e - t_off[i];
-                float a = __fmul_rn(w[0], widen(ld_elem(reinterpret_cast<const T *>(t_src[i]) + r)));
-#pragma unroll
-                for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k - 1] + (e - g.start))), a);
-                st_elem(reinterpret_cast<T *>(t_dst[i]) + r, scale_elem(narrow<T>(a), scale));
-            }
-        }
+    const void *const *op = reinterpret_cast<const void *const *>(out_ptrs);
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, local_ptrs, op, tl.t0, nt);
+        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale);
+    } else {
+        const GlobalView tv = global_view(tb, local_ptrs, op, tl.t0);
+        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale);
     }
 }
 
@@ -763,19 +739,16 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_elem_kernel(KtDeviceTables 
     const KtTile tl = tb.tiles[tile0 + blockIdx.x];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const int nt = tl.nt == 0 ? 1 : tl.nt;
-    TableView tv;
-    tv.off = tb.t_off + tl.t0; tv.numel = tb.t_numel + tl.t0;
-    tv.ptr = reinterpret_cast<const uintptr_t *>(local_ptrs) + tl.t0;
-    const uintptr_t *t_dst = reinterpret_cast<const uintptr_t *>(out_ptrs) + tl.t0;
+    const GlobalView tv = global_view(tb, local_ptrs, reinterpret_cast<const void *const *>(out_ptrs), tl.t0);
     const void *const *pp = peer_ptrs + (int64_t)g.bucket * (K - 1);
     for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
-        const int i = find_owner(tv, nt, e);
+        const int i = find_owner_v(tv, nt, e);
         if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
             const int64_t r = e - tv.off[i];
             float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
             for (int k = 1; k < K; ++k)
                 a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
-            st_elem(reinterpret_cast<T *>(t_dst[i]) + r, scale_elem(narrow<T>(a), scale));
+            st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
         }
     }
 }
@@ -889,6 +862,59 @@ template <> struct SgdVec<uint16_t> {
     }
 };
 
+// Mixed tile: tv.ptr = parameters, tv.ptr2 = momentum of the owning tensor.
+template <typename T, typename V>
+__device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, const T *src,
+                                          const KtSgd &a, int vec_ok)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int PV = SgdVec<T>::PV;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+        const int64_t e0 = g.start + (int64_t)v * VE;
+        int i = find_owner_v(tv, nt, e0);
+        if (vec_ok && i >= 0 && e0 + VE <= b_n) {
+            const int64_t r = e0 - tv.off[i];
+            if (r + VE <= tv.numel[i]) {
+                const uintptr_t pa = tv.ptr[i] + (uintptr_t)r * 4, va = tv.ptr2[i] + (uintptr_t)r * 4;
+                if (((pa | va) & 15u) == 0) {
+                    u32x4 pr[PV], vr[PV];
+                    const u32x4 gr = ld_vec(src + e0);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        pr[h] = ld_vec(reinterpret_cast<const u32x4 *>(pa) + h);
+                        vr[h] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[h] = ld_vec(reinterpret_cast<const u32x4 *>(va) + h);
+                    }
+                    SgdVec<T>::apply(gr, pr, vr, a);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
+                        st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
+                    }
+                    continue;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int q = 0; q < VE; ++q) {
+            const int64_t e = e0 + q;
+            if (e >= b_n) break;
+            while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+            if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
+                const int64_t r = e - tv.off[i];
+                float *pe = reinterpret_cast<float *>(tv.ptr[i]) + r;
+                float *ve = reinterpret_cast<float *>(tv.ptr2[i]) + r;
+                float pv = ld_elem(pe), vv = a.first ? 0.0f : ld_elem(ve);
+                sgd_elem(widen(ld_elem(src + e)), pv, vv, a);
+                st_elem(pe, pv);
+                st_elem(ve, vv);
+            }
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *bucket_ptrs,
@@ -896,9 +922,8 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
                                                                  KtSgd a, int vec_ok)
 {
     constexpr int VE = Elem<T>::VE;
-    constexpr int PV = SgdVec<T>::PV;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
-    __shared__ LdsTable2 lds;
+    __shared__ LdsTable lds;
 
     const KtTile tl = tb.tiles[tile0 + blockIdx.x];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
@@ -957,71 +982,15 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
     }
 
     const int nt = tl.nt == 0 ? 1 : tl.nt;
-    const int64_t *t_off;
-    const int64_t *t_numel;
-    const uintptr_t *t_p;
-    const uintptr_t *t_v;
-    if (nt <= KT_LDS_TENSORS) {
-        for (int i = tid; i < nt; i += KT_BLOCK) {
-            lds.off[i] = tb.t_off[tl.t0 + i];
-            lds.numel[i] = tb.t_numel[tl.t0 + i];
-            lds.src[i] = reinterpret_cast<uintptr_t>(param_ptrs[tl.t0 + i]);
-            lds.dst[i] = reinterpret_cast<uintptr_t>(mom_ptrs[tl.t0 + i]);
-        }
-        __syncthreads();
-        t_off = lds.off; t_numel = lds.numel; t_p = lds.src; t_v = lds.dst;
-    } else {
-        t_off = tb.t_off + tl.t0; t_numel = tb.t_numel + tl.t0;
-        t_p = reinterpret_cast<const uintptr_t *>(param_ptrs) + tl.t0;
-        t_v = reinterpret_cast<const uintptr_t *>(mom_ptrs) + tl.t0;
-    }
-    TableView tv;
-    tv.off = t_off; tv.numel = t_numel; tv.ptr = t_p;
-
     const int64_t b_n = tb.b_elems[g.bucket];
-    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
-#pragma unroll 1
-    for (int v = tid; v < nvec; v += KT_BLOCK) {
-        const int64_t e0 = g.start + (int64_t)v * VE;
-        int i = find_owner(tv, nt, e0);
-        if (vec_ok && i >= 0 && e0 + VE <= b_n) {
-            const int64_t r = e0 - t_off[i];
-            if (r + VE <= t_numel[i]) {
-                const uintptr_t pa = t_p[i] + (uintptr_t)r * 4, va = t_v[i] + (uintptr_t)r * 4;
-                if (((pa | va) & 15u) == 0) {
-                    u32x4 pr[PV], vr[PV];
-                    const u32x4 gr = ld_vec(src + e0);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        pr[h] = ld_vec(reinterpret_cast<const u32x4 *>(pa) + h);
-                        vr[h] = u32x4{0, 0, 0, 0};
-                        if (!a.first) vr[h] = ld_vec(reinterpret_cast<const u32x4 *>(va) + h);
-                    }
-                    SgdVec<T>::apply(gr, pr, vr, a);
-#pragma unroll
-                    for (int h = 0; h < PV; ++h) {
-                        st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
-                        st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
-                    }
-                    continue;
-                }
-            }
-        }
-#pragma unroll 1
-        for (int q = 0; q < VE; ++q) {
-            const int64_t e = e0 + q;
-            if (e >= b_n) break;
-            while (i + 1 < nt && t_off[i + 1] <= e) ++i;
-            if (i >= 0 && e - t_off[i] < t_numel[i]) {
-                const int64_t r = e - t_off[i];
-                float *pe = reinterpret_cast<float *>(t_p[i]) + r;
-                float *ve = reinterpret_cast<float *>(t_v[i]) + r;
-                float pv = ld_elem(pe), vv = a.first ? 0.0f : ld_elem(ve);
-                sgd_elem(widen(ld_elem(src + e)), pv, vv, a);
-                st_elem(pe, pv);
-                st_elem(ve, vv);
-            }
-        }
+    const void *const *pp = reinterpret_cast<const void *const *>(param_ptrs);
+    const void *const *mp = reinterpret_cast<const void *const *>(mom_ptrs);
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, pp, mp, tl.t0, nt);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
+    } else {
+        const GlobalView tv = global_view(tb, pp, mp, tl.t0);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
     }
 }
 
