@@ -57,13 +57,12 @@ def setup(name, dev, in_place=True):
     td = wl.torch_dtype(w.dtype)
     nb = plan.num_buckets
     elems = plan.bucket_elems()
-    peers = [[torch.empty(n, dtype=td, device=dev) for n in elems] for _ in range(K)]
-    # peer slots 1..K-1: other devices' gradients, packed by the same kernel
+    # peer slot 0 receives the packed local gradients; slots 1..K-1 stand for the buckets
+    # that arrive from the other devices: seeded Gaussians written straight into the buffers
+    peers = [[torch.empty(n, dtype=td, device=dev) for n in elems]]
     for k in range(1, K):
-        g = wl.gradient_set(w, k, dev)
-        plan.kt_bucket_pack(-1, g, peers[k])
-        torch.cuda.synchronize()
-        del g
+        peers.append([wl.flat_normal(n, w.dtype, w.sigma, w.seed * 1000 + 100 * k + b, dev)
+                      for b, n in enumerate(elems)])
     local = wl.gradient_set(w, 0, dev)
     # like an AllReduce, the reduce writes its result over peer slot 0 (the C ABI allows the
     # output to be one of the inputs); --out-of-place gives it buffers of its own

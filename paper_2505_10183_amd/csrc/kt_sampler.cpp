@@ -2,6 +2,7 @@
 // receives a portion of every global mini-batch in proportion to its score;
 // Sec. IV-A: the DistributedSampler override).  Host only: the index lists are
 // consumed by the host-side data loader.
+#include <cstddef>
 #include <cstdint>
 #include <numeric>
 #include <vector>
