@@ -1,5 +1,5 @@
 // C ABI of the library: plan objects, argument checks, per-call pointer tables
-// and kernel launches.  Host code; the kernels live in kt_kernels.hip.
+// and kernel launches.  Host code; the kernels live in the .hip files beside it.
 #include <hip/hip_runtime_api.h>
 
 #include <cstdarg>

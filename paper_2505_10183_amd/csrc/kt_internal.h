@@ -60,7 +60,7 @@ struct KtDeviceTables {
     const int64_t *b_elems;
 };
 
-// Launchers (kt_kernels.hip).  `tile0`/`ntiles` select a contiguous tile range.
+// Launchers (defined next to their kernels in the .hip files).  `tile0`/`ntiles` select a contiguous tile range.
 // All return a hipError_t cast to int.
 int kt_launch_pack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                    int64_t ntiles, const void *const *d_tensor_ptrs,

@@ -1,0 +1,147 @@
+// HIP kernels for gfx950: the K-way weighted reduce.  HBM-bound (K reads, one write per
+// element); nothing here is a contraction, so no MFMA.
+#include "kt_device.h"
+
+namespace {
+
+template <typename T, int K>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
+                                                             const void *const *peer_ptrs, KtWeights wts,
+                                                             void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;   // vectors per lane, K loads each, all in flight at once
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const int tid = threadIdx.x;
+
+    const T *x[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) x[k] = reinterpret_cast<const T *>(peer_ptrs[(int64_t)g.bucket * K + k]) + g.start;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
+    float w[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) w[k] = wts.w[k];
+
+    const int64_t n = g.end - g.start;
+    const int nvec = (int)(n / VE);
+
+    if (nvec == KT_TILE_VECS) {
+        u32x4 r[VPT][K];
+#pragma unroll
+        for (int u = 0; u < VPT; ++u)
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + u * KT_BLOCK + tid);
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            Acc<T> acc;
+            acc.first(r[u][0], w[0]);
+#pragma unroll
+            for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
+            st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc.finish());
+        }
+    } else {
+        for (int v = tid; v < nvec; v += KT_BLOCK) {
+            u32x4 r[K];
+#pragma unroll
+            for (int k = 0; k < K; ++k) r[k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + v);
+            Acc<T> acc;
+            acc.first(r[0], w[0]);
+#pragma unroll
+            for (int k = 1; k < K; ++k) acc.add(r[k], w[k]);
+            st_vec(reinterpret_cast<u32x4 *>(out) + v, acc.finish());
+        }
+        // tail of a densely packed bucket (fewer than VE elements)
+        const int64_t e = (int64_t)nvec * VE + tid;
+        if (e < n) {
+            float a = __fmul_rn(w[0], widen(ld_elem(x[0] + e)));
+#pragma unroll
+            for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k] + e)), a);
+            st_elem(out + e, narrow<T>(a));
+        }
+    }
+}
+
+// Any K (weights in the kernel argument block), 16-byte vectors.
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_anyk_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                  const void *const *peer_ptrs, int K,
+                                                                  KtWeights wts, void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const int tid = threadIdx.x;
+    const void *const *pp = peer_ptrs + (int64_t)g.bucket * K;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
+    const int64_t n = g.end - g.start;
+    const int nvec = (int)(n / VE);
+    for (int v = tid; v < nvec; v += KT_BLOCK) {
+        Acc<T> acc;
+        acc.first(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[0]) + g.start) + v), wts.w[0]);
+#pragma unroll 4
+        for (int k = 1; k < K; ++k)
+            acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k]) + g.start) + v), wts.w[k]);
+        st_vec(reinterpret_cast<u32x4 *>(out) + v, acc.finish());
+    }
+    const int64_t e = (int64_t)nvec * VE + tid;
+    if (e < n) {
+        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + g.start + e)));
+        for (int k = 1; k < K; ++k)
+            a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + g.start + e)), a);
+        st_elem(out + e, narrow<T>(a));
+    }
+}
+
+// Any K, any alignment: one element per lane per step.
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_elem_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                  const void *const *peer_ptrs, int K,
+                                                                  KtWeights wts, void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const void *const *pp = peer_ptrs + (int64_t)g.bucket * K;
+    T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]);
+    for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
+        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + e)));
+        for (int k = 1; k < K; ++k) a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + e)), a);
+        st_elem(out + e, narrow<T>(a));
+    }
+}
+
+template <typename T>
+hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntiles, const void *const *peers,
+                           int K, const KtWeights &w, void *const *outs, bool vector_ok, hipStream_t s)
+{
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (!vector_ok) {
+        kt_reduce_elem_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs);
+        return hipGetLastError();
+    }
+    switch (K) {
+#define KT_CASE(KK) \
+    case KK: kt_reduce_kernel<T, KK><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
+        KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
+#undef KT_CASE
+    default: kt_reduce_anyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                     const void *const *d_peer_ptrs, int K, const KtWeights &w, void *const *d_out_ptrs,
+                     bool vector_ok, void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    if (dt == KT_F32) return (int)launch_reduce_t<float>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
+    return (int)launch_reduce_t<uint16_t>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
+}

@@ -1,0 +1,239 @@
+// HIP kernels for gfx950: unpack fused with SGD momentum / weight decay.
+#include "kt_device.h"
+
+namespace {
+
+// ---- unpack fused with SGD (momentum, weight decay) -------------------------
+// With g = scale * bucket value:  g' = fma(wd, p, g);  v' = g' on the first
+// step, else fma(mu, v, g');  p' = fma(-lr, v', p).  p and v are binary32,
+// updated in place; the gradient itself is never written.
+
+__device__ __forceinline__ void sgd_elem(float x, float &p, float &v, const KtSgd &a)
+{
+    const float g = __fmul_rn(a.scale, x);
+    const float g2 = __fmaf_rn(a.wd, p, g);
+    const float vn = a.first ? g2 : __fmaf_rn(a.mu, v, g2);
+    p = __fmaf_rn(-a.lr, vn, p);
+    v = vn;
+}
+
+// four consecutive gradient elements
+template <typename T> struct Quad;
+template <> struct Quad<float> { u32x4 d; };
+template <> struct Quad<uint16_t> { uint32_t d[2]; };
+
+__device__ __forceinline__ Quad<float> ld_quad(const Quad<float> *p)
+{
+    Quad<float> q;
+    q.d = ld_vec(p);
+    return q;
+}
+__device__ __forceinline__ Quad<uint16_t> ld_quad(const Quad<uint16_t> *p)
+{
+    const u32x2 t = __builtin_nontemporal_load((const KT_GLOBAL u32x2 *)p);
+    Quad<uint16_t> q;
+    q.d[0] = t[0];
+    q.d[1] = t[1];
+    return q;
+}
+__device__ __forceinline__ void sgd_quad(const Quad<float> &g, u32x4 &p, u32x4 &v, const KtSgd &a)
+{
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        float pp = __uint_as_float(p[c]), vv = __uint_as_float(v[c]);
+        sgd_elem(__uint_as_float(g.d[c]), pp, vv, a);
+        p[c] = __float_as_uint(pp);
+        v[c] = __float_as_uint(vv);
+    }
+}
+__device__ __forceinline__ void sgd_quad(const Quad<uint16_t> &g, u32x4 &p, u32x4 &v, const KtSgd &a)
+{
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        float p0 = __uint_as_float(p[2 * c]), v0 = __uint_as_float(v[2 * c]);
+        float p1 = __uint_as_float(p[2 * c + 1]), v1 = __uint_as_float(v[2 * c + 1]);
+        sgd_elem(bf16_lo(g.d[c]), p0, v0, a);
+        sgd_elem(bf16_hi(g.d[c]), p1, v1, a);
+        p[2 * c] = __float_as_uint(p0); v[2 * c] = __float_as_uint(v0);
+        p[2 * c + 1] = __float_as_uint(p1); v[2 * c + 1] = __float_as_uint(v1);
+    }
+}
+
+// one 16-byte gradient vector against its 4 (fp32) or 8 (bf16) parameters
+template <typename T> struct SgdVec;
+template <> struct SgdVec<float> {
+    static constexpr int PV = 1;
+    static __device__ __forceinline__ void apply(u32x4 g, u32x4 *p, u32x4 *v, const KtSgd &a)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float pp = __uint_as_float(p[0][c]), vv = __uint_as_float(v[0][c]);
+            sgd_elem(__uint_as_float(g[c]), pp, vv, a);
+            p[0][c] = __float_as_uint(pp);
+            v[0][c] = __float_as_uint(vv);
+        }
+    }
+};
+template <> struct SgdVec<uint16_t> {
+    static constexpr int PV = 2;
+    static __device__ __forceinline__ void apply(u32x4 g, u32x4 *p, u32x4 *v, const KtSgd &a)
+    {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int h = c >> 1, o = (c & 1) * 2;
+            float p0 = __uint_as_float(p[h][o]), v0 = __uint_as_float(v[h][o]);
+            float p1 = __uint_as_float(p[h][o + 1]), v1 = __uint_as_float(v[h][o + 1]);
+            sgd_elem(bf16_lo(g[c]), p0, v0, a);
+            sgd_elem(bf16_hi(g[c]), p1, v1, a);
+            p[h][o] = __float_as_uint(p0); v[h][o] = __float_as_uint(v0);
+            p[h][o + 1] = __float_as_uint(p1); v[h][o + 1] = __float_as_uint(v1);
+        }
+    }
+};
+
+// Mixed tile: tv.ptr = parameters, tv.ptr2 = momentum of the owning tensor.
+template <typename T, typename V>
+__device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, const T *src,
+                                          const KtSgd &a, int vec_ok)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int PV = SgdVec<T>::PV;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+        const int64_t e0 = g.start + (int64_t)v * VE;
+        int i = find_owner_v(tv, nt, e0);
+        if (vec_ok && i >= 0 && e0 + VE <= b_n) {
+            const int64_t r = e0 - tv.off[i];
+            if (r + VE <= tv.numel[i]) {
+                const uintptr_t pa = tv.ptr[i] + (uintptr_t)r * 4, va = tv.ptr2[i] + (uintptr_t)r * 4;
+                if (((pa | va) & 15u) == 0) {
+                    u32x4 pr[PV], vr[PV];
+                    const u32x4 gr = ld_vec(src + e0);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        pr[h] = ld_vec(reinterpret_cast<const u32x4 *>(pa) + h);
+                        vr[h] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[h] = ld_vec(reinterpret_cast<const u32x4 *>(va) + h);
+                    }
+                    SgdVec<T>::apply(gr, pr, vr, a);
+#pragma unroll
+                    for (int h = 0; h < PV; ++h) {
+                        st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
+                        st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
+                    }
+                    continue;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int q = 0; q < VE; ++q) {
+            const int64_t e = e0 + q;
+            if (e >= b_n) break;
+            while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+            if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
+                const int64_t r = e - tv.off[i];
+                float *pe = reinterpret_cast<float *>(tv.ptr[i]) + r;
+                float *ve = reinterpret_cast<float *>(tv.ptr2[i]) + r;
+                float pv = ld_elem(pe), vv = a.first ? 0.0f : ld_elem(ve);
+                sgd_elem(widen(ld_elem(src + e)), pv, vv, a);
+                st_elem(pe, pv);
+                st_elem(ve, vv);
+            }
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                 const void *const *bucket_ptrs,
+                                                                 void *const *param_ptrs, void *const *mom_ptrs,
+                                                                 KtSgd a, int vec_ok)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    __shared__ LdsTable lds;
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const T *src = reinterpret_cast<const T *>(bucket_ptrs[g.bucket]);
+    const int tid = threadIdx.x;
+
+    if (vec_ok && tl.nt == 0) {
+        // Solid tile, processed in quads of 4 elements so that every access is
+        // coalesced: 16 bytes of p and of v per lane, 16 (fp32) or 8 (bf16)
+        // bytes of gradient.
+        const int64_t rel = g.start - tb.t_off[tl.t0];
+        float *pp = reinterpret_cast<float *>(param_ptrs[tl.t0]) + rel;
+        float *vp = reinterpret_cast<float *>(mom_ptrs[tl.t0]) + rel;
+        if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0) {
+            constexpr int QPT = (int)(TILE_ELEMS / 4 / KT_BLOCK);     // quads per lane in a full tile
+            const Quad<T> *s4 = reinterpret_cast<const Quad<T> *>(src + g.start);
+            u32x4 *p4 = reinterpret_cast<u32x4 *>(pp);
+            u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
+            const int nq = (int)((g.end - g.start) / 4);
+            if (nq == QPT * KT_BLOCK) {
+                constexpr int QB = 4;          // quads in flight per lane
+                static_assert(QPT % QB == 0, "quads per lane");
+#pragma unroll 1
+                for (int u0 = 0; u0 < QPT; u0 += QB) {
+                    Quad<T> gr[QB];
+                    u32x4 pr[QB], vr[QB];
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        const int idx = (u0 + u) * KT_BLOCK + tid;
+                        gr[u] = ld_quad(s4 + idx);
+                        pr[u] = ld_vec(p4 + idx);
+                        vr[u] = u32x4{0, 0, 0, 0};
+                        if (!a.first) vr[u] = ld_vec(v4 + idx);
+                    }
+#pragma unroll
+                    for (int u = 0; u < QB; ++u) {
+                        const int idx = (u0 + u) * KT_BLOCK + tid;
+                        sgd_quad(gr[u], pr[u], vr[u], a);
+                        st_vec(p4 + idx, pr[u]);
+                        st_vec(v4 + idx, vr[u]);
+                    }
+                }
+            } else {
+#pragma unroll 1
+                for (int idx = tid; idx < nq; idx += KT_BLOCK) {
+                    const Quad<T> gq = ld_quad(s4 + idx);
+                    u32x4 pr = ld_vec(p4 + idx), vr = u32x4{0, 0, 0, 0};
+                    if (!a.first) vr = ld_vec(v4 + idx);
+                    sgd_quad(gq, pr, vr, a);
+                    st_vec(p4 + idx, pr);
+                    st_vec(v4 + idx, vr);
+                }
+            }
+            return;
+        }
+    }
+
+    const int nt = tl.nt == 0 ? 1 : tl.nt;
+    const int64_t b_n = tb.b_elems[g.bucket];
+    const void *const *pp = reinterpret_cast<const void *const *>(param_ptrs);
+    const void *const *mp = reinterpret_cast<const void *const *>(mom_ptrs);
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, pp, mp, tl.t0, nt);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
+    } else {
+        const GlobalView tv = global_view(tb, pp, mp, tl.t0);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
+    }
+}
+
+}  // namespace
+
+int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
+                         const void *const *d_bucket_ptrs, void *const *d_param_ptrs, void *const *d_mom_ptrs,
+                         const KtSgd &a, bool vector_ok, void *stream)
+{
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    if (dt == KT_F32)
+        kt_unpack_sgd_kernel<float><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+    else
+        kt_unpack_sgd_kernel<uint16_t><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+    return (int)hipGetLastError();
+}
