@@ -191,6 +191,45 @@ def cpu_baseline(st, budget_elems):
                       % (chosen[-1][0], w.name, payload, w.total_elems, secs)}
 
 
+def ceilings(dev, reps=10):
+    """What the memory system sustains on flat 1 GiB buffers, with the library's own kernels:
+    a read-only stream of 8 buffers (kt_probe_read), a plain copy (kt_weighted_reduce with
+    K = 1, w = 1) and the 8:1 read:write mix of the reduce itself.  Context for the roofline
+    fraction: the 8 TB/s peak is not reachable even by pure reads."""
+    import ctypes
+    import torch
+    import paper_2505_10183_amd as kt
+    n = 1 << 28                                   # fp32 elements = 1 GiB per buffer
+    bufs = [torch.empty(n, dtype=torch.float32, device=dev).normal_() for _ in range(8)]
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    plan = kt.Plan([n], "f32", 0, 16)
+    a8, a1, ao = plan.marshal(bufs), plan.marshal(bufs[:1]), plan.marshal([out])
+    w8 = (ctypes.c_float * 8)(*([0.125] * 8))
+    w1 = (ctypes.c_float * 1)(1.0)
+
+    def loop(fn):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e-3
+
+    gib = float(n * 4)
+    t_read = loop(lambda: kt.binding.kt_probe_read(a8, gib, sink))
+    t_copy = loop(lambda: plan.kt_weighted_reduce(-1, a1, 1, w1, ao))
+    t_mix = loop(lambda: plan.kt_weighted_reduce(-1, a8, 8, w8, ao))
+    res = {"buffers": "flat 1 GiB fp32 each", "read_only_8_streams_GBps": round(8 * gib / t_read / 1e9, 1),
+           "copy_GBps": round(2 * gib / t_copy / 1e9, 1), "reduce_8_reads_1_write_GBps": round(9 * gib / t_mix / 1e9, 1)}
+    assert float(sink.abs().sum()) == 0.0
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -203,6 +242,7 @@ def main():
     ap.add_argument("--cpu-elems", type=int, default=0, help="element budget of the CPU baseline sample (0 = auto)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--out-of-place", action="store_true", help="reduce into separate output buffers")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the memory-system probe")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -242,6 +282,7 @@ def main():
         del s2
         torch.cuda.empty_cache()
 
+    ceil = None if args.no_ceilings else ceilings(dev)
     line = {
         "metric": "weighted bucket-reduce+pack/unpack HBM GB/s",
         "value": round(res["step_GBps"], 2),
@@ -268,6 +309,7 @@ def main():
                      "bound": "hbm", "achieved": round(res["reduce_GBps"], 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic(w.name), "traffic_unit": "bytes per launch"},
+        "memory_system": ceil,
         "cpu_baseline": cpu,
         "also": also,
     }

@@ -308,6 +308,23 @@ kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
                                float momentum, float weight_decay,
                                int first_step, void *stream);
 
+/*
+ * Memory-system probe (a measuring aid, not part of the method): streams the
+ * first bytes_each bytes, rounded down to a multiple of 16 KiB, of each of K
+ * (1..8) device buffers through the same 16-byte non-temporal loads and tile
+ * shape as kt_weighted_reduce, and stores nothing.  Timing it gives the
+ * read-only rate the device sustains, the ceiling the read-dominated reduce
+ * can be held against.
+ *
+ *   bufs            host, in : K device pointers, 16-byte aligned.
+ *   sink            device   : 16 writable, 16-byte aligned bytes; written only
+ *                              if the XOR of everything a lane read equals one
+ *                              fixed 128-bit pattern.
+ *   bytes_read_each host, out: optional; bytes actually streamed per buffer.
+ */
+kt_status kt_probe_read(const void *const *bufs, int K, int64_t bytes_each,
+                        void *sink, int64_t *bytes_read_each, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

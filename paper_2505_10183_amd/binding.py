@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp), c.c_float,
                                            c.c_float, c.c_float, i32, vp]
         L.kt_bucket_unpack_sgd.restype = i32
+        L.kt_probe_read.argtypes = [c.POINTER(vp), i32, i64, vp, c.POINTER(i64), vp]
+        L.kt_probe_read.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -122,6 +124,14 @@ def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> T
     w = (ctypes.c_float * max(1, K))() if want_weights else None
     _check(lib().kt_plan_shares(t, K, int(B), b, w))
     return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
+
+
+def kt_probe_read(bufs: Sequence, bytes_each: int, sink, stream=None) -> int:
+    """Enqueue the read-only streaming probe; returns the bytes streamed per buffer."""
+    arr = bufs if isinstance(bufs, ctypes.Array) else _ptr_array(bufs)
+    n = ctypes.c_int64()
+    _check(lib().kt_probe_read(arr, len(arr), int(bytes_each), _ptr(sink), ctypes.byref(n), _stream(stream)))
+    return n.value
 
 
 def kt_replan_shares(step_time: Sequence[float], shares_used: Sequence[int], ema: Sequence[float], alpha: float,

@@ -20,7 +20,7 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wextra",
 def build(verbose: bool = False, extra_defines=()) -> str:
     objs = []
     for name in ("kt_plan.cpp", "kt_sampler.cpp", "kt_api.cpp", "kt_pack_unpack.hip", "kt_reduce.hip",
-                 "kt_fused.hip", "kt_sgd.hip"):
+                 "kt_fused.hip", "kt_sgd.hip", "kt_probe.hip"):
         src = os.path.join(CSRC, name)
         obj = os.path.join(CSRC, os.path.splitext(name)[0] + ".o")
         cmd = [HIPCC] + COMMON + list(extra_defines)

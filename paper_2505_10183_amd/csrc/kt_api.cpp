@@ -584,3 +584,24 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     return mark_used(p, slot, s);
     KT_GUARD_END("kt_bucket_unpack_sgd")
 }
+
+extern "C" kt_status kt_probe_read(const void *const *bufs, int K, int64_t bytes_each, void *sink,
+                                   int64_t *bytes_read_each, void *stream)
+{
+    const char *who = "kt_probe_read";
+    if (!bufs || !sink) { kt_set_error("%s: NULL argument", who); return KT_EINVAL; }
+    if (K < 1 || K > 8) { kt_set_error("%s: K=%d outside [1,8]", who, K); return KT_EINVAL; }
+    if (bytes_each < 0) { kt_set_error("%s: negative size", who); return KT_EINVAL; }
+    if (reinterpret_cast<uintptr_t>(sink) & (KT_VEC_BYTES - 1)) { kt_set_error("%s: sink not 16-byte aligned", who); return KT_EALIGN; }
+    for (int k = 0; k < K; ++k) {
+        if (!bufs[k]) { kt_set_error("%s: NULL buffer %d", who, k); return KT_EINVAL; }
+        if (reinterpret_cast<uintptr_t>(bufs[k]) & (KT_VEC_BYTES - 1)) { kt_set_error("%s: buffer %d not 16-byte aligned", who, k); return KT_EALIGN; }
+    }
+    const int64_t ntiles = bytes_each / KT_TILE_BYTES;
+    if (ntiles * KT_BLOCK >= ((int64_t)1 << 32)) { kt_set_error("%s: more than 2^24 tiles", who); return KT_EUNSUPPORTED; }
+    if (bytes_read_each) *bytes_read_each = ntiles * KT_TILE_BYTES;
+    if (ntiles == 0) return KT_OK;
+    int e = kt_launch_probe_read(bufs, K, ntiles, sink, stream);
+    if (e != 0) return hip_fail("kt_probe_read: launch", (hipError_t)e);
+    return KT_OK;
+}

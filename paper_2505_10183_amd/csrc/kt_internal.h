@@ -97,4 +97,7 @@ int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                          void *const *d_param_ptrs, void *const *d_mom_ptrs,
                          const KtSgd &a, bool vector_ok, void *stream);
 
+int kt_launch_probe_read(const void *const *bufs, int K, int64_t ntiles,
+                         void *sink, void *stream);
+
 #endif

@@ -627,3 +627,13 @@ def test_edge_shapes():
     assert pz.num_buckets == 1 and pz.bucket_elems() == [0] and pz.num_tiles == 0
     pz.kt_bucket_pack(-1, [None, None], [None])
     pz.kt_weighted_reduce(-1, [None], 1, [1.0], [None])
+
+
+def test_probe_read_stores_nothing():
+    bufs = [torch.randn(100000, device=DEV) for _ in range(8)]
+    sink = torch.full((4,), 7.0, device=DEV)
+    for K in (1, 3, 8):
+        got = kt.binding.kt_probe_read(bufs[:K], 100000 * 4, sink)
+        assert got == (100000 * 4 // 16384) * 16384
+    torch.cuda.synchronize()
+    assert bool((sink == 7.0).all())

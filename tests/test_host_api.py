@@ -333,3 +333,14 @@ def test_replan_errors_leave_state_untouched():
     t2 = (ctypes.c_double * 2)(1.0, 1.0)
     assert L.kt_replan_shares(t2, u, e, 0.0, 2, 8, b, None) == 1
     assert L.kt_replan_shares(t2, u, e, 0.5, 2, 8, b, None) == 0 and sum(b) == 8
+
+
+def test_probe_argument_errors_without_gpu():
+    for bufs, nbytes, sink, want in (([4096] * 9, 1 << 20, 8192, "KT_EINVAL"), ([], 1 << 20, 8192, "KT_EINVAL"),
+                                     ([4096, 0], 1 << 20, 8192, "KT_EINVAL"), ([4096, 4100], 1 << 20, 8192, "KT_EALIGN"),
+                                     ([4096], 1 << 20, 8196, "KT_EALIGN"), ([4096], -1, 8192, "KT_EINVAL"),
+                                     ([4096], 1 << 20, 0, "KT_EINVAL")):
+        with pytest.raises(kt.KtError) as ei:
+            kt.binding.kt_probe_read(bufs, nbytes, sink, stream=0)
+        assert ei.value.status_name == want
+    assert kt.binding.kt_probe_read([4096], 16383, 8192, stream=0) == 0     # less than one tile: nothing to do
