@@ -18,7 +18,16 @@ What it computes (KAITIAN, Sec. III and III-C):
 * ``weighted_reduce``  -- out[i] = sum_k w_k * x_k[i], ascending k;
 * ``unpack_scale``     -- g_t[i] = scale * bucket[off_t + i];
 * ``direct``           -- the same end result with no buckets at all:
-                          g_t[i] = scale * sum_k w_k g_t^(k)[i].
+                          g_t[i] = scale * sum_k w_k g_t^(k)[i];
+* ``sampler_epoch``    -- the dataset indices a device processes in an epoch when
+                          every global batch is split by the shares (Sec. III-C
+                          phase 2, Sec. IV-A);
+* ``group_weights``, ``two_level_reduce`` -- reduction inside groups, then
+                          across groups (Sec. III-A);
+* ``unpack_sgd``       -- unpack fused with SGD momentum / weight decay (the
+                          optimizer of Sec. IV-B);
+* ``replan_shares``    -- online adaptation of the shares from measured step
+                          times (Sec. III-C phase 1).
 
 Element arithmetic lives in ``kt_oracle.c`` (plain C, doubles); integer
 planning is plain Python below.  Arrays are numpy: float32 for fp32 data,
