@@ -46,7 +46,7 @@ def measured_traffic(workload):
     return TRAFFIC_BYTES.get(workload)
 
 
-def setup(name, dev, in_place=True):
+def setup(name, dev, in_place=True, misalign=False):
     import torch
     import paper_2505_10183_amd as kt
     from paper_2505_10183_amd import workloads as wl
@@ -60,14 +60,15 @@ def setup(name, dev, in_place=True):
     elems = plan.bucket_elems()
     # peer slot 0 receives the packed local gradients; slots 1..K-1 stand for the buckets
     # that arrive from the other devices: seeded Gaussians written straight into the buffers
-    peers = [[torch.empty(n, dtype=td, device=dev) for n in elems]]
+    sh = 1 if misalign else 0        # element offset of every bucket buffer inside its allocation
+    peers = [[torch.empty(n + sh, dtype=td, device=dev)[sh:] for n in elems]]
     for k in range(1, K):
-        peers.append([wl.flat_normal(n, w.dtype, w.sigma, w.seed * 1000 + 100 * k + b, dev)
+        peers.append([wl.flat_normal(n + sh, w.dtype, w.sigma, w.seed * 1000 + 100 * k + b, dev)[sh:]
                       for b, n in enumerate(elems)])
     local = wl.gradient_set(w, 0, dev)
     # like an AllReduce, the reduce writes its result over peer slot 0 (the C ABI allows the
     # output to be one of the inputs); --out-of-place gives it buffers of its own
-    outs = peers[0] if in_place else [torch.empty(n, dtype=td, device=dev) for n in elems]
+    outs = peers[0] if in_place else [torch.empty(n + sh, dtype=td, device=dev)[sh:] for n in elems]
     result = [torch.empty_like(t) for t in local]
     st = {
         "w": w, "plan": plan, "K": K, "weights": weights, "shares": shares, "nb": nb,
@@ -94,9 +95,9 @@ def step(st, scale=1.0, ev=None):
     p.kt_bucket_unpack_scale(-1, st["a_outs"], scale, st["a_result"])
 
 
-def time_workload(name, steps, warmup, dev, in_place=True):
+def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     import torch
-    st = setup(name, dev, in_place)
+    st = setup(name, dev, in_place, misalign)
     w = st["w"]
     for _ in range(warmup):
         step(st)
@@ -243,6 +244,11 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--out-of-place", action="store_true", help="reduce into separate output buffers")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the memory-system probe")
+    ap.add_argument("--lib", default="", help="load this build of libkt.so instead of the in-tree one "
+                                              "(variants made with paper_2505_10183_amd/build.py --out)")
+    ap.add_argument("--misalign", action="store_true",
+                    help="offset every bucket buffer by one element: the library then takes its "
+                         "element-wise (4-byte / 2-byte) kernels instead of the 16-byte ones")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -251,6 +257,9 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    if args.lib:
+        from paper_2505_10183_amd import binding
+        binding.LIB_PATH = os.path.abspath(args.lib)
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU available", file=sys.stderr)
@@ -267,7 +276,7 @@ def main():
         del a, b
         torch.cuda.empty_cache()
 
-    res, st = time_workload(args.workload, args.steps, args.warmup, dev, not args.out_of_place)
+    res, st = time_workload(args.workload, args.steps, args.warmup, dev, not args.out_of_place, args.misalign)
     w = st["w"]
     cpu = None
     if not args.no_cpu:
@@ -277,7 +286,7 @@ def main():
     del st
     torch.cuda.empty_cache()
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
-        r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place)
+        r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place, args.misalign)
         also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
         del s2
         torch.cuda.empty_cache()
@@ -300,7 +309,8 @@ def main():
                                % (w.name, len(w.shapes), w.total_elems, w.dtype, w.K, w.global_batch,
                                   res["buckets"], w.bucket_cap_bytes >> 20),
                    "launch": "one batched launch per kernel over all buckets; reduce %s"
-                             % ("into its own output buffers" if args.out_of_place else "in place over peer slot 0"),
+                             % ("into its own output buffers" if args.out_of_place else "in place over peer slot 0")
+                             + ("; buckets misaligned by one element (element-wise kernels)" if args.misalign else ""),
                    "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
         "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
         "buckets_per_s": round(res["buckets_per_s"], 1),

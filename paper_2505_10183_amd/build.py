@@ -17,12 +17,17 @@ COMMON = ["-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wextra",
           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def build(verbose: bool = False, extra_defines=()) -> str:
+def build(verbose: bool = False, extra_defines=(), out: str = LIB) -> str:
+    """Compile and link the library.  `extra_defines` are passed to every
+    compile (-DKT_TILE_BYTES=8192, -DKT_NT_LOAD=0, -DKT_NT_STORE=0,
+    -DKT_LDS_TENSORS=1 build the variants used to compare design choices);
+    `out` names the shared library to write (default: the in-tree libkt.so)."""
     objs = []
+    tag = "" if out == LIB else ".variant%d" % os.getpid()
     for name in ("kt_plan.cpp", "kt_sampler.cpp", "kt_api.cpp", "kt_pack_unpack.hip", "kt_reduce.hip",
                  "kt_fused.hip", "kt_sgd.hip", "kt_probe.hip"):
         src = os.path.join(CSRC, name)
-        obj = os.path.join(CSRC, os.path.splitext(name)[0] + ".o")
+        obj = os.path.join(CSRC, os.path.splitext(name)[0] + tag + ".o")
         cmd = [HIPCC] + COMMON + list(extra_defines)
         if name.endswith(".hip"):
             cmd += DEVICE_FLAGS
@@ -31,14 +36,23 @@ def build(verbose: bool = False, extra_defines=()) -> str:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)
         objs.append(obj)
-    tmp = LIB + ".tmp%d" % os.getpid()
+    tmp = out + ".tmp%d" % os.getpid()
     cmd = [HIPCC, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", tmp] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    if tag:
+        for o in objs:
+            os.remove(o)
+    return out
 
 
 if __name__ == "__main__":
-    print(build(verbose=True, extra_defines=sys.argv[1:]))
+    args = sys.argv[1:]
+    target = LIB
+    if "--out" in args:
+        i = args.index("--out")
+        target = os.path.abspath(args[i + 1])
+        del args[i:i + 2]
+    print(build(verbose=True, extra_defines=args, out=target))

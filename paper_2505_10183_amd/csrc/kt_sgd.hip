@@ -173,7 +173,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
             u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
             const int nq = (int)((g.end - g.start) / 4);
             if (nq == QPT * KT_BLOCK) {
-                constexpr int QB = 4;          // quads in flight per lane
+                constexpr int QB = QPT < 4 ? QPT : 4;     // quads in flight per lane
                 static_assert(QPT % QB == 0, "quads per lane");
 #pragma unroll 1
                 for (int u0 = 0; u0 < QPT; u0 += QB) {
