@@ -138,6 +138,20 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     a_p, a_v = p.marshal(params), p.marshal(moms)
     ms_sgd = loop(lambda: p.kt_bucket_unpack_sgd(-1, st["a_outs"], 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False))
     del params, moms
+    # the chained step recorded once into a HIP graph and replayed (launch-bound small sets)
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step(st)
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    ms_graph = (time.perf_counter() - t0) * 1e3 / steps
+    del graph
     e, s, K = w.total_elems, w.elem_size, st["K"]
     res = {
         "workload": name, "elements": e, "buckets": st["nb"], "K": K,
@@ -152,6 +166,8 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
         "fused_ms": ms_fused, "fused_GBps": (K + 1) * s * e / (ms_fused * 1e-3) / 1e9,
         "fused_buckets_per_s": st["nb"] / (ms_fused * 1e-3),
         "unpack_sgd_ms": ms_sgd, "unpack_sgd_GBps": (s + 16) * e / (ms_sgd * 1e-3) / 1e9,
+        "graph_step_ms": ms_graph, "graph_step_GBps": (K + 5) * s * e / (ms_graph * 1e-3) / 1e9,
+        "graph_buckets_per_s": st["nb"] / (ms_graph * 1e-3),
     }
     return res, st
 

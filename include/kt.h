@@ -29,6 +29,12 @@
  *    pointers are checked and dereferenced on the device.  Passing the same
  *    array contents on successive calls lets the library reuse its resident
  *    device copy instead of uploading it again.
+ *  - HIP graphs: a device call may be recorded under stream capture once the
+ *    same call (same plan, same pointer arrays) has been made outside capture,
+ *    so that the plan's tables and the pointer table are resident; under
+ *    capture the library enqueues its kernel and nothing else.  A pointer table
+ *    used by a captured call stays resident until the plan is destroyed (a
+ *    plan holds 8 tables).  Otherwise the call returns KT_EUNSUPPORTED.
  */
 #ifndef KT_H
 #define KT_H

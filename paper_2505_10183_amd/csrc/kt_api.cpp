@@ -44,6 +44,14 @@ static kt_status hip_fail(const char *what, hipError_t e)
     return e == hipErrorOutOfMemory ? KT_ENOMEM : KT_EHIP;
 }
 
+// True while `s` is recording into a HIP graph.  Under capture the library only
+// enqueues kernels: it uploads nothing, allocates nothing and records no events.
+static bool capturing(hipStream_t s)
+{
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    return hipStreamIsCapturing(s, &st) == hipSuccess && st == hipStreamCaptureStatusActive;
+}
+
 // No exception may cross the C boundary.
 #define KT_GUARD_BEGIN try {
 #define KT_GUARD_END(who)                                              \
@@ -73,6 +81,7 @@ struct PtrSlot {
     uint64_t last_seq = 0;              // plan-wide sequence number of that launch
     bool multi_stream = false;
     bool valid = false;
+    bool in_graph = false;              // read by a launch recorded under stream capture: never reused
     uint64_t stamp = 0;
 };
 
@@ -186,8 +195,13 @@ extern "C" kt_status kt_plan_tile_info(const kt_plan *p, int64_t i, int *bucket,
 }
 
 // Upload the plan tables on the first device call.  Caller holds p->mu.
-static kt_status ensure_device(kt_plan *p)
+static kt_status ensure_device(kt_plan *p, hipStream_t stream)
 {
+    if (p->device < 0 && capturing(stream)) {
+        kt_set_error("the first device call on a plan uploads its tables and cannot be recorded into a graph; "
+                     "make one call outside stream capture first");
+        return KT_EUNSUPPORTED;
+    }
     int cur = -1;
     hipError_t e = hipGetDevice(&cur);
     if (e != hipSuccess) return hip_fail("hipGetDevice", e);
@@ -232,8 +246,14 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
     for (PtrSlot &s : p->slots) {
         if (s.valid && s.n == n && memcmp(s.pinned, vals, n * 8) == 0) { hit = &s; break; }
     }
+    const bool cap = capturing(stream);
     if (hit) {
-        if (hit->upload_stream != stream) {
+        if (cap) {
+            // a graph keeps using this table for as long as it is replayed
+            e = hipEventSynchronize(hit->uploaded);
+            if (e != hipSuccess) return hip_fail("hipEventSynchronize", e);
+            hit->in_graph = true;
+        } else if (hit->upload_stream != stream) {
             e = hipStreamWaitEvent(stream, hit->uploaded, 0);
             if (e != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
         }
@@ -241,9 +261,19 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
         *slot_out = hit;
         return KT_OK;
     }
+    if (cap) {
+        kt_set_error("these pointers have no resident table yet and an upload cannot be recorded into a graph; "
+                     "make the same call once outside stream capture first");
+        return KT_EUNSUPPORTED;
+    }
     for (PtrSlot &s : p->slots) {
+        if (s.in_graph) continue;
         if (!s.valid) { victim = &s; break; }
         if (!victim || s.stamp < victim->stamp) victim = &s;
+    }
+    if (!victim) {
+        kt_set_error("all %d pointer tables of this plan are referenced by captured graphs", KT_SLOTS);
+        return KT_EUNSUPPORTED;
     }
     if (victim->valid) {
         // the upload and the launches that read this table must have finished
@@ -295,6 +325,7 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
 // Bookkeeping after a launch that read `s` on `stream`.  Caller holds p->mu.
 static kt_status mark_used(kt_plan *p, PtrSlot *s, hipStream_t stream)
 {
+    if (s->in_graph && capturing(stream)) return KT_OK;   // the table stays resident for good
     if (s->last_seq > 0 && s->use_stream != stream) s->multi_stream = true;
     s->use_stream = stream;
     s->last_seq = ++p->seq;
@@ -363,7 +394,7 @@ static kt_status prepare_tensor_call(kt_plan *p, int bucket, const void *const *
         }
     }
     *vector_ok = vec;
-    st = ensure_device(p);
+    st = ensure_device(p, stream);
     if (st != KT_OK) return st;
     return stage_pointers(p, vals.data(), vals.size(), stream, slot);
 }
@@ -453,7 +484,7 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     KtWeights w;
     memset(&w, 0, sizeof w);
     for (int k = 0; k < K; ++k) w.w[k] = weights[k];
-    st = ensure_device(p);
+    st = ensure_device(p, s);
     if (st != KT_OK) return st;
     PtrSlot *slot = nullptr;
     st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
@@ -517,7 +548,7 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
     KtWeights w;
     memset(&w, 0, sizeof w);
     for (int k = 0; k < K; ++k) w.w[k] = weights[k];
-    st = ensure_device(p);
+    st = ensure_device(p, s);
     if (st != KT_OK) return st;
     PtrSlot *slot = nullptr;
     st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
@@ -570,7 +601,7 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
             }
         }
     }
-    st = ensure_device(p);
+    st = ensure_device(p, s);
     if (st != KT_OK) return st;
     PtrSlot *slot = nullptr;
     st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
