@@ -109,8 +109,12 @@ def _ptr_array(items: Sequence) -> ctypes.Array:
 
 def _stream(stream) -> int:
     if stream is None:
+        # torch's current stream on the current device, as a raw hipStream_t
         import torch
-        return torch.cuda.current_stream().cuda_stream
+        try:
+            return torch._C._cuda_getCurrentRawStream(torch._C._cuda_getDevice())
+        except AttributeError:
+            return torch.cuda.current_stream().cuda_stream
     if isinstance(stream, int):
         return stream
     return stream.cuda_stream

@@ -346,6 +346,15 @@ static kt_status mark_used(kt_plan *p, PtrSlot *s, hipStream_t stream)
     return KT_OK;
 }
 
+// Per-thread scratch for the pointer table of the current call: no heap
+// allocation once it has grown to the size a caller needs.
+static std::vector<uint64_t> &call_table(size_t n)
+{
+    static thread_local std::vector<uint64_t> tbl;
+    tbl.resize(n);
+    return tbl;
+}
+
 // Resolve the bucket selector into a bucket range and a tile range.
 static kt_status select(const kt_plan *p, int bucket, const char *who, int *b0, int *b1, int64_t *tile0, int64_t *ntiles)
 {
@@ -375,7 +384,7 @@ static kt_status prepare_tensor_call(kt_plan *p, int bucket, const void *const *
     // The whole arrays go into the table (so that per-bucket calls made with
     // the same arrays share one resident table); only the selected buckets'
     // entries are validated and dereferenced.
-    std::vector<uint64_t> vals(T + nb, 0);
+    std::vector<uint64_t> &vals = call_table(T + nb);
     for (size_t t = 0; t < T; ++t) vals[t] = reinterpret_cast<uintptr_t>(tensor_ptrs[t]);
     for (size_t b = 0; b < nb; ++b) vals[T + b] = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
     bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
@@ -459,7 +468,7 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     const KtHostPlan &hp = p->hp;
     const size_t nb = hp.b_elems.size();
     const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
-    std::vector<uint64_t> vals(nb * K + nb, 0);
+    std::vector<uint64_t> &vals = call_table(nb * K + nb);
     for (size_t i = 0; i < nb * K; ++i) vals[i] = reinterpret_cast<uintptr_t>(peer_bufs[i]);
     for (size_t b = 0; b < nb; ++b) vals[nb * K + b] = reinterpret_cast<uintptr_t>(out_bufs[b]);
     bool vec = true;
@@ -517,7 +526,7 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
     const size_t T = hp.t_numel.size(), nb = hp.b_elems.size(), KP = (size_t)(K - 1);
     const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
     // table layout: [local tensors T | output tensors T | peers nb*(K-1)]
-    std::vector<uint64_t> vals(2 * T + nb * KP, 0);
+    std::vector<uint64_t> &vals = call_table(2 * T + nb * KP);
     for (size_t t = 0; t < T; ++t) {
         vals[t] = reinterpret_cast<uintptr_t>(local_tensor_ptrs[t]);
         vals[T + t] = reinterpret_cast<uintptr_t>(out_tensor_ptrs[t]);
@@ -579,7 +588,7 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     const KtHostPlan &hp = p->hp;
     const size_t T = hp.t_numel.size(), nb = hp.b_elems.size();
     // table layout: [parameters T | momentum T | buckets nb]
-    std::vector<uint64_t> vals(2 * T + nb, 0);
+    std::vector<uint64_t> &vals = call_table(2 * T + nb);
     for (size_t t = 0; t < T; ++t) {
         vals[t] = reinterpret_cast<uintptr_t>(param_ptrs[t]);
         vals[T + t] = reinterpret_cast<uintptr_t>(momentum_ptrs[t]);

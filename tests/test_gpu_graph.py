@@ -119,3 +119,31 @@ def test_capture_refuses_unprepared_calls():
     plan.kt_bucket_pack(-1, a, b2)
     torch.cuda.synchronize()
     assert torch.equal(b2[0][:5000], a[0])
+
+
+def test_tables_used_by_graphs_are_never_reused():
+    """A plan keeps 8 pointer tables; each captured call pins one.  The ninth
+    distinct pointer set can still run eagerly only if a table is free, and
+    is refused with a clear error otherwise."""
+    plan = kt.Plan([4096], "f32", 0, 16)
+    src = [torch.randn(4096, device=DEV)]
+    graphs, bufs = [], []
+    for i in range(8):
+        b = [torch.zeros(4096, device=DEV)]
+        plan.kt_bucket_pack(-1, src, b)          # eager: table resident
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            plan.kt_bucket_pack(-1, src, b)
+        graphs.append(g)
+        bufs.append(b)
+    extra = [torch.zeros(4096, device=DEV)]
+    with pytest.raises(kt.KtError) as ei:
+        plan.kt_bucket_pack(-1, src, extra)
+    assert ei.value.status_name == "KT_EUNSUPPORTED"
+    src[0].copy_(torch.arange(4096, device=DEV, dtype=torch.float32))
+    for g in graphs:
+        g.replay()
+    torch.cuda.synchronize()
+    for b in bufs:
+        assert torch.equal(b[0], src[0])
