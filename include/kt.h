@@ -32,9 +32,21 @@
  *  - HIP graphs: a device call may be recorded under stream capture once the
  *    same call (same plan, same pointer arrays) has been made outside capture,
  *    so that the plan's tables and the pointer table are resident; under
- *    capture the library enqueues its kernel and nothing else.  A pointer table
- *    used by a captured call stays resident until the plan is destroyed (a
- *    plan holds 8 tables).  Otherwise the call returns KT_EUNSUPPORTED.
+ *    capture the library enqueues its kernel and nothing else.  Otherwise the
+ *    call returns KT_EUNSUPPORTED.  A pointer table read by a recorded call is
+ *    set aside for the graph and stays resident until the plan is destroyed
+ *    (one table per distinct pointer set: a chained step records three, pack,
+ *    reduce and unpack; tables of eager calls are not affected).
+ *    Everything passed by value is frozen into the recorded kernel node: the K
+ *    weights, scale, lr, momentum, weight_decay and first_step.  After new
+ *    shares (kt_replan_shares) or a learning-rate change a replayed graph
+ *    still applies the old values: record the step again, or update the
+ *    kernel node's parameters.  A recorded first_step != 0 would reset the
+ *    momentum on every replay, so kt_bucket_unpack_sgd refuses it under
+ *    capture (KT_EUNSUPPORTED).
+ *  - Streams passed to device calls should outlive the plan.  If the stream of
+ *    an earlier call has been destroyed, the library waits for the whole
+ *    device instead of that stream when it recycles a pointer table.
  */
 #ifndef KT_H
 #define KT_H
@@ -313,23 +325,6 @@ kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
                                void *const *momentum_ptrs, float lr,
                                float momentum, float weight_decay,
                                int first_step, void *stream);
-
-/*
- * Memory-system probe (a measuring aid, not part of the method): streams the
- * first bytes_each bytes, rounded down to a multiple of 16 KiB, of each of K
- * (1..8) device buffers through the same 16-byte non-temporal loads and tile
- * shape as kt_weighted_reduce, and stores nothing.  Timing it gives the
- * read-only rate the device sustains, the ceiling the read-dominated reduce
- * can be held against.
- *
- *   bufs            host, in : K device pointers, 16-byte aligned.
- *   sink            device   : 16 writable, 16-byte aligned bytes; written only
- *                              if the XOR of everything a lane read equals one
- *                              fixed 128-bit pattern.
- *   bytes_read_each host, out: optional; bytes actually streamed per buffer.
- */
-kt_status kt_probe_read(const void *const *bufs, int K, int64_t bytes_each,
-                        void *sink, int64_t *bytes_read_each, void *stream);
 
 #ifdef __cplusplus
 }

@@ -72,8 +72,6 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp), c.c_float,
                                            c.c_float, c.c_float, i32, vp]
         L.kt_bucket_unpack_sgd.restype = i32
-        L.kt_probe_read.argtypes = [c.POINTER(vp), i32, i64, vp, c.POINTER(i64), vp]
-        L.kt_probe_read.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -130,14 +128,6 @@ def kt_plan_shares(thr: Sequence[float], B: int, want_weights: bool = True) -> T
     return [int(b[i]) for i in range(K)], ([float(w[i]) for i in range(K)] if want_weights else None)
 
 
-def kt_probe_read(bufs: Sequence, bytes_each: int, sink, stream=None) -> int:
-    """Enqueue the read-only streaming probe; returns the bytes streamed per buffer."""
-    arr = bufs if isinstance(bufs, ctypes.Array) else _ptr_array(bufs)
-    n = ctypes.c_int64()
-    _check(lib().kt_probe_read(arr, len(arr), int(bytes_each), _ptr(sink), ctypes.byref(n), _stream(stream)))
-    return n.value
-
-
 def kt_replan_shares(step_time: Sequence[float], shares_used: Sequence[int], ema: Sequence[float], alpha: float,
                      B: int):
     """One online-adaptation step: (new_ema, shares, weights)."""
@@ -192,6 +182,7 @@ class Plan:
         h = ctypes.c_void_p()
         _check(lib().kt_plan_create(arr, T, _DTYPES[dtype], int(cap_bytes), int(align_bytes), ctypes.byref(h)))
         self._h = h
+        self._nb = lib().kt_plan_num_buckets(h)
 
     def close(self):
         if getattr(self, "_h", None):
@@ -206,7 +197,7 @@ class Plan:
 
     @property
     def num_buckets(self) -> int:
-        return lib().kt_plan_num_buckets(self._h)
+        return self._nb
 
     @property
     def num_tensors(self) -> int:
@@ -235,46 +226,66 @@ class Plan:
         return [self.bucket_info(b)[0] for b in range(self.num_buckets)]
 
     # -- device calls: marshal pointers, call, raise on error ---------------
+    # The library copies whole arrays (T tensor pointers, num_buckets bucket
+    # pointers, num_buckets * K peer pointers) whatever bucket is selected, so
+    # every array's length is checked here before its address crosses the ABI.
 
     def marshal(self, items: Sequence) -> ctypes.Array:
         """Pre-marshalled pointer array (reusable across calls)."""
         return _ptr_array(items)
 
-    def _arr(self, items):
-        return items if isinstance(items, ctypes.Array) else _ptr_array(items)
+    def _arr(self, items, want: int, what: str):
+        pre = isinstance(items, ctypes.Array)
+        # marshal() pads an empty list to one (unused) entry
+        if len(items) != (max(1, want) if pre else want):
+            raise ValueError("%s: need %d entries (the library copies the whole array whatever bucket is "
+                             "selected), got %d" % (what, want, len(items)))
+        return items if pre else _ptr_array(items)
+
+    def _weights(self, weights, K: int):
+        if len(weights) != K:
+            raise ValueError("need K = %d weights, got %d" % (K, len(weights)))
+        if isinstance(weights, ctypes.Array):
+            return weights
+        return (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
 
     def kt_bucket_pack(self, bucket: int, tensors, bucket_bufs, stream=None):
-        _check(lib().kt_bucket_pack(self._h, bucket, self._arr(tensors), self._arr(bucket_bufs), _stream(stream)))
+        T, nb = len(self.numels), self.num_buckets
+        _check(lib().kt_bucket_pack(self._h, bucket, self._arr(tensors, T, "tensor_ptrs"),
+                                    self._arr(bucket_bufs, nb, "bucket_bufs"), _stream(stream)))
 
     def kt_weighted_reduce(self, bucket: int, peer_bufs, K: int, weights, out_bufs, stream=None):
         """peer_bufs: flat sequence, entry [b * K + k]."""
-        if isinstance(weights, ctypes.Array):
-            w = weights
-        else:
-            w = (ctypes.c_float * max(1, len(weights)))(*[float(x) for x in weights])
-            if len(weights) != K:
-                raise ValueError("need K weights")
-        _check(lib().kt_weighted_reduce(self._h, bucket, self._arr(peer_bufs), K, w, self._arr(out_bufs),
+        nb = self.num_buckets
+        if not 1 <= K <= KT_MAX_PEERS:      # the library rejects K before it reads any array
+            _check(lib().kt_weighted_reduce(self._h, bucket, None, K, None, None, _stream(stream)))
+        _check(lib().kt_weighted_reduce(self._h, bucket, self._arr(peer_bufs, nb * K, "peer_bufs"), K,
+                                        self._weights(weights, K), self._arr(out_bufs, nb, "bucket_bufs (outputs)"),
                                         _stream(stream)))
 
     def kt_bucket_unpack_scale(self, bucket: int, bucket_bufs, scale: float, tensors, stream=None):
-        _check(lib().kt_bucket_unpack_scale(self._h, bucket, self._arr(bucket_bufs), float(scale),
-                                            self._arr(tensors), _stream(stream)))
+        T, nb = len(self.numels), self.num_buckets
+        _check(lib().kt_bucket_unpack_scale(self._h, bucket, self._arr(bucket_bufs, nb, "bucket_bufs"), float(scale),
+                                            self._arr(tensors, T, "tensor_ptrs"), _stream(stream)))
+
+    def _fused(self, fn, bucket, local_tensors, peer_bufs, K, weights, scale, out_tensors, stream):
+        T, nb = len(self.numels), self.num_buckets
+        if not 1 <= K <= KT_MAX_PEERS:      # the library rejects K before it reads any array
+            _check(fn(self._h, bucket, None, None, K, None, float(scale), None, _stream(stream)))
+        _check(fn(self._h, bucket, self._arr(local_tensors, T, "tensor_ptrs (local)"),
+                  self._arr(peer_bufs, nb * (K - 1), "peer_bufs"), K, self._weights(weights, K), float(scale),
+                  self._arr(out_tensors, T, "tensor_ptrs (outputs)"), _stream(stream)))
 
     def kt_fused_step(self, bucket: int, local_tensors, peer_bufs, K: int, weights, scale: float, out_tensors,
                       stream=None):
         """peer_bufs: flat sequence over peers 1..K-1, entry [b * (K-1) + (k-1)]."""
-        if isinstance(weights, ctypes.Array):
-            w = weights
-        else:
-            if len(weights) != K:
-                raise ValueError("need K weights")
-            w = (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
-        _check(lib().kt_fused_step(self._h, bucket, self._arr(local_tensors), self._arr(peer_bufs), K, w,
-                                   float(scale), self._arr(out_tensors), _stream(stream)))
+        self._fused(lib().kt_fused_step, bucket, local_tensors, peer_bufs, K, weights, scale, out_tensors, stream)
 
     def kt_bucket_unpack_sgd(self, bucket: int, bucket_bufs, scale: float, params, momenta, lr: float,
                              momentum: float, weight_decay: float, first_step: bool, stream=None):
-        _check(lib().kt_bucket_unpack_sgd(self._h, bucket, self._arr(bucket_bufs), float(scale), self._arr(params),
-                                          self._arr(momenta), float(lr), float(momentum), float(weight_decay),
-                                          int(bool(first_step)), _stream(stream)))
+        T, nb = len(self.numels), self.num_buckets
+        _check(lib().kt_bucket_unpack_sgd(self._h, bucket, self._arr(bucket_bufs, nb, "bucket_bufs"), float(scale),
+                                          self._arr(params, T, "tensor_ptrs (parameters)"),
+                                          self._arr(momenta, T, "tensor_ptrs (momentum)"), float(lr),
+                                          float(momentum), float(weight_decay), int(bool(first_step)),
+                                          _stream(stream)))

@@ -25,7 +25,7 @@ def build(verbose: bool = False, extra_defines=(), out: str = LIB) -> str:
     objs = []
     tag = "" if out == LIB else ".variant%d" % os.getpid()
     for name in ("kt_plan.cpp", "kt_sampler.cpp", "kt_api.cpp", "kt_pack_unpack.hip", "kt_reduce.hip",
-                 "kt_fused.hip", "kt_sgd.hip", "kt_probe.hip"):
+                 "kt_fused.hip", "kt_sgd.hip"):
         src = os.path.join(CSRC, name)
         obj = os.path.join(CSRC, os.path.splitext(name)[0] + tag + ".o")
         cmd = [HIPCC] + COMMON + list(extra_defines)
@@ -48,6 +48,23 @@ def build(verbose: bool = False, extra_defines=(), out: str = LIB) -> str:
     return out
 
 
+PROBE_SRC = os.path.join(ROOT, "bench_probe.hip")
+PROBE_LIB = os.path.join(ROOT, "libkt_bench_probe.so")
+
+
+def build_bench_probe(verbose: bool = False) -> str:
+    """Compile the benchmark's read-only bandwidth probe (bench_probe.hip beside
+    bench.py) into its own small shared library; the C-ABI library does not
+    contain it."""
+    tmp = PROBE_LIB + ".tmp%d" % os.getpid()
+    cmd = [HIPCC, "-O3", "-std=c++17", "-fPIC", "-shared"] + DEVICE_FLAGS + [PROBE_SRC, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     args = sys.argv[1:]
     target = LIB
@@ -56,3 +73,5 @@ if __name__ == "__main__":
         target = os.path.abspath(args[i + 1])
         del args[i:i + 2]
     print(build(verbose=True, extra_defines=args, out=target))
+    if target == LIB:
+        print(build_bench_probe(verbose=True))

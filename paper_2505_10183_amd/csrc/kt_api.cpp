@@ -2,6 +2,7 @@
 // and kernel launches.  Host code; the kernels live in the .hip files beside it.
 #include <hip/hip_runtime_api.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -85,6 +86,14 @@ struct PtrSlot {
     uint64_t stamp = 0;
 };
 
+static void release_slot(PtrSlot &s)
+{
+    if (s.dev) (void)hipFree(s.dev);
+    if (s.pinned) (void)hipHostFree(s.pinned);
+    if (s.uploaded) (void)hipEventDestroy(s.uploaded);
+    s = PtrSlot();
+}
+
 // Before a table is overwritten, the launches that read it must have finished.
 // Recording an event after every launch would put a marker between all kernels;
 // instead every KT_TICK_EVERY-th launch records a "tick" event carrying the
@@ -107,7 +116,12 @@ struct kt_plan {
     int device = -1;
     void *dev_blob = nullptr;
     KtDeviceTables tb{};
+    uint64_t serial = 0;   // identifies the plan for the lifetime of the process
     PtrSlot slots[KT_SLOTS];
+    // Tables read by launches recorded into HIP graphs: moved out of the ring
+    // (so that eager calls keep all KT_SLOTS tables) and kept until the plan
+    // is destroyed, because a graph may be replayed at any time.
+    std::vector<PtrSlot *> graph_tables;
     Tick ticks[KT_TICKS];
     int tick_head = 0;
     uint64_t seq = 0;      // launches issued through this plan
@@ -132,9 +146,14 @@ extern "C" kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt, in
         delete p;
         return st;
     }
+    static std::atomic<uint64_t> next_serial{1};
+    p->serial = next_serial.fetch_add(1);
     *out = p;
     return KT_OK;
 }
+
+const KtHostPlan &kt_plan_host(const kt_plan *p) { return p->hp; }
+uint64_t kt_plan_serial(const kt_plan *p) { return p->serial; }
 
 extern "C" kt_status kt_plan_destroy(kt_plan *p)
 {
@@ -146,11 +165,8 @@ extern "C" kt_status kt_plan_destroy(kt_plan *p)
         if (cur != p->device) (void)hipSetDevice(p->device);
         hipError_t e = hipDeviceSynchronize();
         if (e != hipSuccess) st = hip_fail("kt_plan_destroy: hipDeviceSynchronize", e);
-        for (PtrSlot &s : p->slots) {
-            if (s.dev) (void)hipFree(s.dev);
-            if (s.pinned) (void)hipHostFree(s.pinned);
-            if (s.uploaded) (void)hipEventDestroy(s.uploaded);
-        }
+        for (PtrSlot &s : p->slots) release_slot(s);
+        for (PtrSlot *g : p->graph_tables) { release_slot(*g); delete g; }
         for (Tick &t : p->ticks)
             if (t.ev) (void)hipEventDestroy(t.ev);
         if (p->dev_blob) (void)hipFree(p->dev_blob);
@@ -237,23 +253,61 @@ static kt_status ensure_device(kt_plan *p, hipStream_t stream)
     return KT_OK;
 }
 
+// Wait until every launch that read table `v` has finished.  Caller holds p->mu.
+static hipError_t wait_retired(kt_plan *p, const PtrSlot *v)
+{
+    hipError_t e;
+    if (v->last_seq == 0) {
+        e = hipEventSynchronize(v->uploaded);
+    } else if (v->multi_stream) {
+        return hipDeviceSynchronize();
+    } else {
+        const Tick *best = nullptr;
+        for (const Tick &t : p->ticks)
+            if (t.valid && t.stream == v->use_stream && t.seq >= v->last_seq && (!best || t.seq < best->seq))
+                best = &t;
+        e = best ? hipEventSynchronize(best->ev) : hipStreamSynchronize(v->use_stream);
+    }
+    if (e != hipSuccess) {
+        // e.g. the caller destroyed the stream of that launch: the targeted wait is
+        // impossible, waiting for the whole device is always sufficient
+        (void)hipGetLastError();
+        e = hipDeviceSynchronize();
+    }
+    return e;
+}
+
 // Make `vals[0..n)` resident on the device for a launch on `stream`.
 // Caller holds p->mu.  On success *slot_out is the slot to mark after launch.
 static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipStream_t stream, PtrSlot **slot_out)
 {
     hipError_t e;
+    const bool cap = capturing(stream);
+    for (PtrSlot *g : p->graph_tables) {
+        if (g->n == n && memcmp(g->pinned, vals, n * 8) == 0) {
+            // its upload was waited for when it was moved here
+            *slot_out = g;
+            return KT_OK;
+        }
+    }
     PtrSlot *hit = nullptr, *victim = nullptr;
     for (PtrSlot &s : p->slots) {
         if (s.valid && s.n == n && memcmp(s.pinned, vals, n * 8) == 0) { hit = &s; break; }
     }
-    const bool cap = capturing(stream);
     if (hit) {
         if (cap) {
-            // a graph keeps using this table for as long as it is replayed
+            // A graph keeps using this table for as long as it is replayed: take
+            // it out of the ring, whose slot becomes free for eager calls again.
             e = hipEventSynchronize(hit->uploaded);
             if (e != hipSuccess) return hip_fail("hipEventSynchronize", e);
-            hit->in_graph = true;
-        } else if (hit->upload_stream != stream) {
+            PtrSlot *g = new PtrSlot(*hit);
+            g->in_graph = true;
+            p->graph_tables.push_back(g);
+            *hit = PtrSlot();
+            *slot_out = g;
+            return KT_OK;
+        }
+        if (hit->upload_stream != stream) {
             e = hipStreamWaitEvent(stream, hit->uploaded, 0);
             if (e != hipSuccess) return hip_fail("hipStreamWaitEvent", e);
         }
@@ -267,27 +321,12 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
         return KT_EUNSUPPORTED;
     }
     for (PtrSlot &s : p->slots) {
-        if (s.in_graph) continue;
         if (!s.valid) { victim = &s; break; }
         if (!victim || s.stamp < victim->stamp) victim = &s;
     }
-    if (!victim) {
-        kt_set_error("all %d pointer tables of this plan are referenced by captured graphs", KT_SLOTS);
-        return KT_EUNSUPPORTED;
-    }
     if (victim->valid) {
         // the upload and the launches that read this table must have finished
-        if (victim->last_seq == 0) {
-            e = hipEventSynchronize(victim->uploaded);
-        } else if (victim->multi_stream) {
-            e = hipDeviceSynchronize();
-        } else {
-            const Tick *best = nullptr;
-            for (const Tick &t : p->ticks)
-                if (t.valid && t.stream == victim->use_stream && t.seq >= victim->last_seq && (!best || t.seq < best->seq))
-                    best = &t;
-            e = best ? hipEventSynchronize(best->ev) : hipStreamSynchronize(victim->use_stream);
-        }
+        e = wait_retired(p, victim);
         if (e != hipSuccess) return hip_fail("waiting for a pointer table to retire", e);
     }
     victim->valid = false;
@@ -325,7 +364,7 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
 // Bookkeeping after a launch that read `s` on `stream`.  Caller holds p->mu.
 static kt_status mark_used(kt_plan *p, PtrSlot *s, hipStream_t stream)
 {
-    if (s->in_graph && capturing(stream)) return KT_OK;   // the table stays resident for good
+    if (s->in_graph) return KT_OK;   // the table stays resident until the plan is destroyed
     if (s->last_seq > 0 && s->use_stream != stream) s->multi_stream = true;
     s->use_stream = stream;
     s->last_seq = ++p->seq;
@@ -506,27 +545,24 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     KT_GUARD_END("kt_weighted_reduce")
 }
 
-extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
-                                   const void *const *peer_bufs, int K, const float *weights, float scale,
-                                   void *const *out_tensor_ptrs, void *stream)
+kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                           const void *const *peer_bufs, int K, const float *weights,
+                           void *const *out_tensor_ptrs, const char *who, std::vector<uint64_t> &vals,
+                           KtWeights *w, int64_t *tile0, int64_t *ntiles, bool *vector_ok)
 {
-    KT_GUARD_BEGIN
-    const char *who = "kt_fused_step";
+    *ntiles = 0;
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
     if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
-    std::lock_guard<std::mutex> lock(p->mu);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     int b0, b1;
-    int64_t tile0, ntiles;
-    kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
-    if (st != KT_OK || ntiles == 0) return st;
+    kt_status st = select(p, bucket, who, &b0, &b1, tile0, ntiles);
+    if (st != KT_OK || *ntiles == 0) return st;
     if (!local_tensor_ptrs || !out_tensor_ptrs || (K > 1 && !peer_bufs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
     const KtHostPlan &hp = p->hp;
     const size_t T = hp.t_numel.size(), nb = hp.b_elems.size(), KP = (size_t)(K - 1);
     const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
     // table layout: [local tensors T | output tensors T | peers nb*(K-1)]
-    std::vector<uint64_t> &vals = call_table(2 * T + nb * KP);
+    vals.resize(2 * T + nb * KP);
     for (size_t t = 0; t < T; ++t) {
         vals[t] = reinterpret_cast<uintptr_t>(local_tensor_ptrs[t]);
         vals[T + t] = reinterpret_cast<uintptr_t>(out_tensor_ptrs[t]);
@@ -554,16 +590,36 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
             }
         }
     }
+    memset(w, 0, sizeof *w);
+    for (int k = 0; k < K; ++k) w->w[k] = weights[k];
+    *vector_ok = vec;
+    return KT_OK;
+}
+
+extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                                   const void *const *peer_bufs, int K, const float *weights, float scale,
+                                   void *const *out_tensor_ptrs, void *stream)
+{
+    KT_GUARD_BEGIN
+    const char *who = "kt_fused_step";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t tile0 = 0, ntiles = 0;
+    bool vec = false;
     KtWeights w;
-    memset(&w, 0, sizeof w);
-    for (int k = 0; k < K; ++k) w.w[k] = weights[k];
+    std::vector<uint64_t> &vals = call_table(0);
+    kt_status st = kt_fused_prepare(p, bucket, local_tensor_ptrs, peer_bufs, K, weights, out_tensor_ptrs, who, vals, &w,
+                                    &tile0, &ntiles, &vec);
+    if (st != KT_OK || ntiles == 0) return st;
+    const size_t T = p->hp.t_numel.size();
     st = ensure_device(p, s);
     if (st != KT_OK) return st;
     PtrSlot *slot = nullptr;
     st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
     if (st != KT_OK) return st;
     const uint64_t *d = static_cast<const uint64_t *>(slot->dev);
-    int e = kt_launch_fused(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d),
+    int e = kt_launch_fused(p->tb, p->hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d),
                             reinterpret_cast<const void *const *>(d + 2 * T), K, w, scale,
                             reinterpret_cast<void *const *>(const_cast<uint64_t *>(d + T)), vec, stream);
     if (e != 0) return hip_fail("kt_fused_step: launch", (hipError_t)e);
@@ -585,6 +641,11 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
     if (st != KT_OK || ntiles == 0) return st;
     if (!bucket_bufs || !param_ptrs || !momentum_ptrs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    if (first_step && capturing(s)) {
+        kt_set_error("%s: first_step is frozen into a recorded kernel and would reset the momentum on every replay; "
+                     "make the first step outside stream capture", who);
+        return KT_EUNSUPPORTED;
+    }
     const KtHostPlan &hp = p->hp;
     const size_t T = hp.t_numel.size(), nb = hp.b_elems.size();
     // table layout: [parameters T | momentum T | buckets nb]
@@ -623,25 +684,4 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     if (e != 0) return hip_fail("kt_bucket_unpack_sgd: launch", (hipError_t)e);
     return mark_used(p, slot, s);
     KT_GUARD_END("kt_bucket_unpack_sgd")
-}
-
-extern "C" kt_status kt_probe_read(const void *const *bufs, int K, int64_t bytes_each, void *sink,
-                                   int64_t *bytes_read_each, void *stream)
-{
-    const char *who = "kt_probe_read";
-    if (!bufs || !sink) { kt_set_error("%s: NULL argument", who); return KT_EINVAL; }
-    if (K < 1 || K > 8) { kt_set_error("%s: K=%d outside [1,8]", who, K); return KT_EINVAL; }
-    if (bytes_each < 0) { kt_set_error("%s: negative size", who); return KT_EINVAL; }
-    if (reinterpret_cast<uintptr_t>(sink) & (KT_VEC_BYTES - 1)) { kt_set_error("%s: sink not 16-byte aligned", who); return KT_EALIGN; }
-    for (int k = 0; k < K; ++k) {
-        if (!bufs[k]) { kt_set_error("%s: NULL buffer %d", who, k); return KT_EINVAL; }
-        if (reinterpret_cast<uintptr_t>(bufs[k]) & (KT_VEC_BYTES - 1)) { kt_set_error("%s: buffer %d not 16-byte aligned", who, k); return KT_EALIGN; }
-    }
-    const int64_t ntiles = bytes_each / KT_TILE_BYTES;
-    if (ntiles * KT_BLOCK >= ((int64_t)1 << 32)) { kt_set_error("%s: more than 2^24 tiles", who); return KT_EUNSUPPORTED; }
-    if (bytes_read_each) *bytes_read_each = ntiles * KT_TILE_BYTES;
-    if (ntiles == 0) return KT_OK;
-    int e = kt_launch_probe_read(bufs, K, ntiles, sink, stream);
-    if (e != 0) return hip_fail("kt_probe_read: launch", (hipError_t)e);
-    return KT_OK;
 }

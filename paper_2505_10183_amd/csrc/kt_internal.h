@@ -82,12 +82,6 @@ int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                     float scale, void *const *d_out_ptrs, bool vector_ok,
                     void *stream);
 
-int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
-                    int64_t ntiles, const void *const *d_local_ptrs,
-                    const void *const *d_peer_ptrs, int K, const KtWeights &w,
-                    float scale, void *const *d_out_ptrs, bool vector_ok,
-                    void *stream);
-
 struct KtSgd {
     float scale, lr, mu, wd;
     int first;
@@ -97,7 +91,22 @@ int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                          void *const *d_param_ptrs, void *const *d_mom_ptrs,
                          const KtSgd &a, bool vector_ok, void *stream);
 
-int kt_launch_probe_read(const void *const *bufs, int K, int64_t ntiles,
-                         void *sink, void *stream);
+// ---- shared between the C ABI (kt_api.cpp) and the entry point that
+// allocates nothing (kt_static.hip) ------------------------------------------
+
+void kt_set_error(const char *fmt, ...);
+
+// The immutable host tables of a plan and a number that identifies the plan
+// for the lifetime of the process (never reused).
+const KtHostPlan &kt_plan_host(const kt_plan *p);
+uint64_t kt_plan_serial(const kt_plan *p);
+
+// Argument checks of the fused single pass and its pointer table
+// [local tensors T | output tensors T | peers nb*(K-1)] written to `vals`
+// (2T + nb*(K-1) entries).  *ntiles == 0 on return means nothing to do.
+kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                           const void *const *peer_bufs, int K, const float *weights,
+                           void *const *out_tensor_ptrs, const char *who, std::vector<uint64_t> &vals,
+                           KtWeights *w, int64_t *tile0, int64_t *ntiles, bool *vector_ok);
 
 #endif

@@ -121,14 +121,15 @@ def test_capture_refuses_unprepared_calls():
     assert torch.equal(b2[0][:5000], a[0])
 
 
-def test_tables_used_by_graphs_are_never_reused():
-    """A plan keeps 8 pointer tables; each captured call pins one.  The ninth
-    distinct pointer set can still run eagerly only if a table is free, and
-    is refused with a clear error otherwise."""
+def test_tables_used_by_graphs_do_not_consume_the_eager_ring():
+    """A pointer table read by a recorded call is set aside for the graph (kept
+    until the plan is destroyed) and frees its place in the ring of 8 tables
+    that eager calls use: after more captures than the ring has places, eager
+    calls with new pointer sets keep working and every graph still replays."""
     plan = kt.Plan([4096], "f32", 0, 16)
     src = [torch.randn(4096, device=DEV)]
     graphs, bufs = [], []
-    for i in range(8):
+    for i in range(12):
         b = [torch.zeros(4096, device=DEV)]
         plan.kt_bucket_pack(-1, src, b)          # eager: table resident
         torch.cuda.synchronize()
@@ -137,13 +138,98 @@ def test_tables_used_by_graphs_are_never_reused():
             plan.kt_bucket_pack(-1, src, b)
         graphs.append(g)
         bufs.append(b)
-    extra = [torch.zeros(4096, device=DEV)]
-    with pytest.raises(kt.KtError) as ei:
+    # more distinct eager pointer sets than the ring holds, interleaved with replays
+    for i in range(20):
+        extra = [torch.zeros(4096, device=DEV)]
         plan.kt_bucket_pack(-1, src, extra)
-    assert ei.value.status_name == "KT_EUNSUPPORTED"
+        graphs[i % 12].replay()
+        torch.cuda.synchronize()
+        assert torch.equal(extra[0], src[0])
+    # an eager call with the pointers of a recorded one shares the graph's table
+    plan.kt_bucket_pack(-1, src, bufs[3])
     src[0].copy_(torch.arange(4096, device=DEV, dtype=torch.float32))
     for g in graphs:
         g.replay()
     torch.cuda.synchronize()
     for b in bufs:
         assert torch.equal(b[0], src[0])
+
+
+def test_recorded_weights_are_frozen_until_the_step_is_recorded_again():
+    """Weights, scale and the SGD scalars travel as kernel arguments: a graph
+    recorded before new shares were planned keeps applying the old weights when
+    replayed; recording the step again applies the new ones.  A first SGD step
+    cannot be recorded at all (it would reset the momentum on every replay)."""
+    K = 3
+    w = wl.ragged_workload(dtype="f32", K=K, seed=77, n_tensors=30)
+    plan = kt.Plan(w.numels, "f32", w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    peers = [[wl.flat_normal(n, "f32", 1e-3, 40 * k + b, DEV) for b, n in enumerate(plan.bucket_elems())] for k in range(K)]
+    flat = [peers[k][b] for b in range(nb) for k in range(K)]
+    outs = [torch.empty_like(t) for t in peers[0]]
+    B = 96
+    shares_a, w_a = kt.kt_plan_shares([1.0, 0.5, 0.5], B)
+    # online adaptation: device 0 turned out slower than planned
+    _, shares_b, w_b = kt.kt_replan_shares([3.0, 1.0, 1.0], shares_a, [0.0] * K, 1.0, B)
+    assert shares_b != shares_a
+    hp = [[host(peers[k][b]) for k in range(K)] for b in range(nb)]
+
+    def expect(wts):
+        wv = np.array(wts, np.float32)
+        return [oracle.weighted_reduce(hp[b], wv, "f32", "S") for b in range(nb)]
+
+    def same(want):
+        torch.cuda.synchronize()
+        return all(raw(host(outs[b])).tobytes() == raw(want[b]).tobytes() for b in range(nb))
+
+    plan.kt_weighted_reduce(-1, flat, K, w_a, outs)
+    assert same(expect(w_a))
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        plan.kt_weighted_reduce(-1, flat, K, w_a, outs)
+    for o in outs:
+        o.zero_()
+    g.replay()
+    assert same(expect(w_a))
+    # eager calls see the new weights at once ...
+    plan.kt_weighted_reduce(-1, flat, K, w_b, outs)
+    assert same(expect(w_b))
+    # ... the old recording does not
+    g.replay()
+    assert same(expect(w_a)) and not same(expect(w_b))
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2):
+        plan.kt_weighted_reduce(-1, flat, K, w_b, outs)
+    for o in outs:
+        o.zero_()
+    g2.replay()
+    assert same(expect(w_b))
+
+    # SGD: a first step is refused under capture, a later step is recorded
+    params = [torch.randn(n, device=DEV) for n in w.numels]
+    moms = [torch.zeros(n, device=DEV) for n in w.numels]
+    plan.kt_bucket_unpack_sgd(-1, outs, 1.0, params, moms, 0.1, 0.9, 5e-4, True)
+    torch.cuda.synchronize()
+    g3 = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    err = None
+    with torch.cuda.stream(s):
+        g3.capture_begin()
+        try:
+            plan.kt_bucket_unpack_sgd(-1, outs, 1.0, params, moms, 0.1, 0.9, 5e-4, True)
+        except kt.KtError as e:
+            err = e
+        plan.kt_bucket_unpack_sgd(-1, outs, 1.0, params, moms, 0.1, 0.9, 5e-4, False)
+        g3.capture_end()
+    assert err is not None and err.status_name == "KT_EUNSUPPORTED"
+    torch.cuda.synchronize()
+    hp_, hv_ = [host(p) for p in params], [host(v) for v in moms]
+    L = oracle.assign_buckets(w.numels, 4, w.bucket_cap_bytes, 16)
+    hb = [host(o) for o in outs]
+    for r in range(2):
+        g3.replay()
+        torch.cuda.synchronize()
+        hp_, hv_ = oracle.unpack_sgd(L, hb, w.numels, 1.0, hp_, hv_, 0.1, 0.9, 5e-4, False, "f32", "S")
+        for t in range(len(w.numels)):
+            assert raw(host(params[t])).tobytes() == raw(hp_[t]).tobytes(), (r, t)
+            assert raw(host(moms[t])).tobytes() == raw(hv_[t]).tobytes(), (r, t)

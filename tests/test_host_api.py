@@ -335,12 +335,27 @@ def test_replan_errors_leave_state_untouched():
     assert L.kt_replan_shares(t2, u, e, 0.5, 2, 8, b, None) == 0 and sum(b) == 8
 
 
-def test_probe_argument_errors_without_gpu():
-    for bufs, nbytes, sink, want in (([4096] * 9, 1 << 20, 8192, "KT_EINVAL"), ([], 1 << 20, 8192, "KT_EINVAL"),
-                                     ([4096, 0], 1 << 20, 8192, "KT_EINVAL"), ([4096, 4100], 1 << 20, 8192, "KT_EALIGN"),
-                                     ([4096], 1 << 20, 8196, "KT_EALIGN"), ([4096], -1, 8192, "KT_EINVAL"),
-                                     ([4096], 1 << 20, 0, "KT_EINVAL")):
-        with pytest.raises(kt.KtError) as ei:
-            kt.binding.kt_probe_read(bufs, nbytes, sink, stream=0)
-        assert ei.value.status_name == want
-    assert kt.binding.kt_probe_read([4096], 16383, 8192, stream=0) == 0     # less than one tile: nothing to do
+def test_binding_rejects_arrays_of_the_wrong_length():
+    """The library copies whole pointer arrays whatever bucket is selected; the
+    binding, which knows T, the bucket count and K, refuses arrays of any other
+    length before an address crosses the C ABI."""
+    p = kt.Plan([70000, 10, 70000], "f32", 100000, 16)
+    assert p.num_buckets == 3
+    t3, b3 = [4096, 8192, 12288], [1 << 20, 2 << 20, 3 << 20]
+    bad = [
+        lambda: p.kt_bucket_pack(1, [8192], [2 << 20], stream=0),                 # "this bucket's" tensors only
+        lambda: p.kt_bucket_pack(1, t3, [2 << 20], stream=0),
+        lambda: p.kt_bucket_pack(-1, t3 + [1], b3, stream=0),
+        lambda: p.kt_bucket_unpack_scale(0, b3[:1], 1.0, t3, stream=0),
+        lambda: p.kt_weighted_reduce(0, [1 << 20, 5 << 20], 2, [0.5, 0.5], b3, stream=0),   # needs 3 * 2 peers
+        lambda: p.kt_weighted_reduce(-1, b3 + b3, 2, [0.5], b3, stream=0),
+        lambda: p.kt_weighted_reduce(-1, b3 + b3, 2, [0.5, 0.5], b3[:2], stream=0),
+        lambda: p.kt_fused_step(-1, t3, b3[:2], 2, [0.5, 0.5], 1.0, t3, stream=0),
+        lambda: p.kt_fused_step(-1, t3[:2], b3, 2, [0.5, 0.5], 1.0, t3, stream=0),
+        lambda: p.kt_bucket_unpack_sgd(-1, b3, 1.0, t3, t3[:2], 0.1, 0.9, 0.0, True, stream=0),
+        lambda: p.kt_bucket_unpack_sgd(-1, b3[:1], 1.0, t3, t3, 0.1, 0.9, 0.0, True, stream=0),
+        lambda: p.kt_bucket_pack(-1, p.marshal(t3[:2]), p.marshal(b3), stream=0),     # pre-marshalled arrays too
+    ]
+    for fn in bad:
+        with pytest.raises(ValueError):
+            fn()
