@@ -85,14 +85,20 @@ def setup(name, dev, in_place=True, misalign=False):
 
 
 def step(st, scale=1.0, ev=None):
+    """One pass of the path.  `ev`: four events recorded on the stream the kernels are
+    launched on (torch's current stream): step start, after pack, after reduce, step end."""
     p = st["plan"]
-    p.kt_bucket_pack(-1, st["a_local"], st["a_slot0"])
     if ev is not None:
         ev[0].record()
-    p.kt_weighted_reduce(-1, st["a_peers"], st["K"], st["a_w"], st["a_outs"])
+    p.kt_bucket_pack(-1, st["a_local"], st["a_slot0"])
     if ev is not None:
         ev[1].record()
+    p.kt_weighted_reduce(-1, st["a_peers"], st["K"], st["a_w"], st["a_outs"])
+    if ev is not None:
+        ev[2].record()
     p.kt_bucket_unpack_scale(-1, st["a_outs"], scale, st["a_result"])
+    if ev is not None:
+        ev[3].record()
 
 
 def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
@@ -102,7 +108,7 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     for _ in range(warmup):
         step(st)
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    evs = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(4)) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
@@ -110,7 +116,9 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / steps
-    ms_reduce = sum(a.elapsed_time(b) for a, b in evs) / steps
+    ms_reduce = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
+    per_step = sorted(e[0].elapsed_time(e[3]) for e in evs)
+    per_reduce = sorted(e[1].elapsed_time(e[2]) for e in evs)
     # pack and unpack alone, each over its own event-bracketed loop (context only)
     p = st["plan"]
 
@@ -131,6 +139,9 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     # chained step, never mixed into `value`
     ms_fused = loop(lambda: p.kt_fused_step(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0,
                                             st["a_result"]))
+    # the same pass writing its result over the local gradients (what a gradient hook does)
+    ms_fused_inplace = loop(lambda: p.kt_fused_step(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0,
+                                                    st["a_local"]))
     # unpack fused with SGD momentum / weight decay: reads the bucket, p and v, writes p and v
     import torch as _t
     params = [_t.zeros(t.numel(), dtype=_t.float32, device=dev) for t in st["local"]]
@@ -161,6 +172,8 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     res = {
         "workload": name, "elements": e, "buckets": st["nb"], "K": K,
         "ms_per_step": ms_step,
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
+        "reduce_ms_median": per_reduce[len(per_reduce) // 2], "reduce_ms_min": per_reduce[0],
         "step_GBps": (K + 5) * s * e / (ms_step * 1e-3) / 1e9,
         "buckets_per_s": st["nb"] / (ms_step * 1e-3),
         "reduce_ms_in_step": ms_reduce,
@@ -170,6 +183,7 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
         "unpack_ms": ms_unpack, "unpack_GBps": 2 * s * e / (ms_unpack * 1e-3) / 1e9,
         "fused_ms": ms_fused, "fused_GBps": (K + 1) * s * e / (ms_fused * 1e-3) / 1e9,
         "fused_buckets_per_s": st["nb"] / (ms_fused * 1e-3),
+        "fused_inplace_ms": ms_fused_inplace, "fused_inplace_GBps": (K + 1) * s * e / (ms_fused_inplace * 1e-3) / 1e9,
         "unpack_sgd_ms": ms_sgd, "unpack_sgd_GBps": (s + 16) * e / (ms_sgd * 1e-3) / 1e9,
     }
     if ms_graph:
@@ -178,47 +192,98 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     return res, st
 
 
+def host_threads():
+    """(cores the host reports, threads the baseline uses).  The thread count is capped by
+    the CPU share the machine grants a job (its OMP_NUM_THREADS setting), not by the core count."""
+    cores = os.cpu_count() or 1
+    try:
+        cores_usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores_usable = cores
+    cap = int(os.environ.get("OMP_NUM_THREADS", "0") or 0) or 16
+    return cores, max(1, min(cores_usable, cap))
+
+
 def cpu_baseline(st, budget_elems):
-    """The CPU checker (as it stands, one thread) on the first buckets of the
-    same workload, same inputs: pack + reduce + unpack-scale once."""
-    import numpy as np
+    """The CPU checker as it stands (strict binary32 mode S: the arithmetic the GPU path
+    performs) on the same workload, same inputs, one pack + reduce + unpack-scale pass per
+    bucket: first on one host thread over the first buckets, then with one bucket per thread
+    on all the threads this job may use, over up to two rounds of buckets."""
+    from concurrent.futures import ThreadPoolExecutor
     import oracle
     from paper_2505_10183_amd import workloads as wl
 
     w, plan, K = st["w"], st["plan"], st["K"]
     nb = st["nb"]
-    chosen, total = [], 0
-    for b in range(nb):
-        n, first, cnt = plan.bucket_info(b)
-        if chosen and total + n > budget_elems:
-            break
-        chosen.append((b, n, first, cnt))
-        total += n
+    cores, threads = host_threads()
     wts = oracle.share_weights(oracle.plan_shares(w.throughputs, w.global_batch), w.global_batch)
-    secs = 0.0
-    payload = 0
-    for b, n, first, cnt in chosen:
+
+    def fetch(b):
+        n, first, cnt = plan.bucket_info(b)
         numels = w.numels[first:first + cnt]
         lay = oracle.assign_buckets(numels, w.elem_size, 0, 16)
         loc = [wl.to_host_array(st["local"][t]) for t in range(first, first + cnt)]
         others = [wl.to_host_array(st["peers"][k][b]) for k in range(1, K)]
-        t0 = time.perf_counter()
+        return lay, numels, loc, others
+
+    def one_bucket(item):
+        lay, numels, loc, others = item
         slot0 = oracle.pack(lay, loc, w.dtype)[0]
-        red = oracle.weighted_reduce([slot0] + others, wts, w.dtype, "D")
-        oracle.unpack_scale(lay, [red], numels, 1.0, w.dtype, "D")
-        secs += time.perf_counter() - t0
-        payload += sum(numels)
-    gbps = (K + 5) * w.elem_size * payload / secs / 1e9
-    return {"value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "buckets 0..%d of %s (%d of %d elements), one pack+reduce+unpack pass, %.1f s"
-                      % (chosen[-1][0], w.name, payload, w.total_elems, secs)}
+        red = oracle.weighted_reduce([slot0] + others, wts, w.dtype, "S")
+        oracle.unpack_scale(lay, [red], numels, 1.0, w.dtype, "S")
+        return sum(numels)
+
+    def pick(limit_elems, limit_buckets):
+        chosen, total = [], 0
+        for b in range(nb):
+            n = plan.bucket_info(b)[0]
+            if chosen and (total + n > limit_elems or len(chosen) >= limit_buckets):
+                break
+            chosen.append(b)
+            total += n
+        return chosen
+
+    single = pick(budget_elems, nb)
+    items = [fetch(b) for b in single]
+    t0 = time.perf_counter()
+    payload1 = sum(one_bucket(it) for it in items)
+    secs1 = time.perf_counter() - t0
+    many = pick(8 * budget_elems, 2 * threads)
+    items += [fetch(b) for b in many[len(single):]]
+    items = items[:len(many)]
+    with ThreadPoolExecutor(threads) as pool:
+        t0 = time.perf_counter()
+        payloadN = sum(pool.map(one_bucket, items))
+        secsN = time.perf_counter() - t0
+    bytes_per_elem = (K + 5) * w.elem_size
+    return {"value": bytes_per_elem * payloadN / secsN / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "mode": "S (binary32 product, then fused multiply-adds in ascending k)",
+            "threads_used": threads, "host_cores": cores,
+            "single_thread_value": bytes_per_elem * payload1 / secs1 / 1e9,
+            "sample": "buckets 0..%d of %s (%d of %d elements), one pack+reduce+unpack pass, one bucket per "
+                      "thread on %d threads, %.1f s" % (many[-1], w.name, payloadN, w.total_elems, threads, secsN),
+            "single_thread_sample": "buckets 0..%d (%d elements), the same pass on one thread, %.1f s"
+                                    % (single[-1], payload1, secs1)}
+
+
+def load_probe():
+    """bench_probe.hip built beside this file (libkt_bench_probe.so); None if it is not built."""
+    import ctypes
+    path = os.path.join(ROOT, "libkt_bench_probe.so")
+    if not os.path.exists(path):
+        return None
+    lib = ctypes.CDLL(path)
+    lib.bench_probe_read.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_int, ctypes.c_int64, ctypes.c_void_p,
+                                     ctypes.c_void_p]
+    lib.bench_probe_read.restype = ctypes.c_int64
+    return lib
 
 
 def ceilings(dev, reps=10):
-    """What the memory system sustains on flat 1 GiB buffers, with the library's own kernels:
-    a read-only stream of 8 buffers (kt_probe_read), a plain copy (kt_weighted_reduce with
-    K = 1, w = 1) and the 8:1 read:write mix of the reduce itself.  Context for the roofline
-    fraction: the 8 TB/s peak is not reachable even by pure reads."""
+    """What the memory system sustains on flat 1 GiB buffers: a read-only stream of 8 buffers
+    (bench_probe.hip: the reduce's loads with nothing stored), a plain copy (kt_weighted_reduce
+    with K = 1, w = 1) and the 8:1 read:write mix of the reduce itself, in place and out of
+    place.  Context for the roofline fraction: the 8 TB/s peak is not reachable even by pure reads."""
     import ctypes
     import torch
     import paper_2505_10183_amd as kt
@@ -227,7 +292,7 @@ def ceilings(dev, reps=10):
     out = torch.empty(n, dtype=torch.float32, device=dev)
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     plan = kt.Plan([n], "f32", 0, 16)
-    a8, a1, ao = plan.marshal(bufs), plan.marshal(bufs[:1]), plan.marshal([out])
+    a8, a1, ao, a0 = plan.marshal(bufs), plan.marshal(bufs[:1]), plan.marshal([out]), plan.marshal(bufs[:1])
     w8 = (ctypes.c_float * 8)(*([0.125] * 8))
     w1 = (ctypes.c_float * 1)(1.0)
 
@@ -244,11 +309,21 @@ def ceilings(dev, reps=10):
         return a.elapsed_time(b) / reps * 1e-3
 
     gib = float(n * 4)
-    t_read = loop(lambda: kt.binding.kt_probe_read(a8, gib, sink))
+    res = {"buffers": "flat 1 GiB fp32 each"}
+    probe = load_probe()
+    if probe is not None:
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def read_only():
+            got = probe.bench_probe_read(a8, 8, int(gib), sink.data_ptr(), stream)
+            assert got == int(gib), got
+        res["read_only_8_streams_GBps"] = round(8 * gib / loop(read_only) / 1e9, 1)
     t_copy = loop(lambda: plan.kt_weighted_reduce(-1, a1, 1, w1, ao))
     t_mix = loop(lambda: plan.kt_weighted_reduce(-1, a8, 8, w8, ao))
-    res = {"buffers": "flat 1 GiB fp32 each", "read_only_8_streams_GBps": round(8 * gib / t_read / 1e9, 1),
-           "copy_GBps": round(2 * gib / t_copy / 1e9, 1), "reduce_8_reads_1_write_GBps": round(9 * gib / t_mix / 1e9, 1)}
+    t_mix_in = loop(lambda: plan.kt_weighted_reduce(-1, a8, 8, w8, a0))
+    res.update({"copy_GBps": round(2 * gib / t_copy / 1e9, 1),
+                "reduce_8_reads_1_write_GBps": round(9 * gib / t_mix / 1e9, 1),
+                "reduce_8_reads_1_write_in_place_GBps": round(9 * gib / t_mix_in / 1e9, 1)})
     assert float(sink.abs().sum()) == 0.0
     return res
 
@@ -302,7 +377,7 @@ def main():
     w = st["w"]
     cpu = None
     if not args.no_cpu:
-        budget = args.cpu_elems or (300_000_000 if w.dtype == "bf16" else 900_000_000)
+        budget = args.cpu_elems or (200_000_000 if w.dtype == "bf16" else 400_000_000)
         try:
             cpu = cpu_baseline(st, budget)
         except Exception as exc:                 # noqa: BLE001
@@ -333,6 +408,8 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(res["ms_per_step"], 5),
+        "ms_per_step_median": round(res["ms_per_step_median"], 5),
+        "ms_per_step_min": round(res["ms_per_step_min"], 5),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -347,11 +424,14 @@ def main():
                    "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
         "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
         "buckets_per_s": round(res["buckets_per_s"], 1),
-        "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone", "_per_s")) and k != "buckets_per_s"},
+        "kernels": {k: round(v, 4) for k, v in res.items() if k.endswith(("_ms", "_GBps", "_in_step", "_alone", "_per_s", "_median", "_min"))
+                    and k not in ("buckets_per_s", "ms_per_step_median", "ms_per_step_min")},
         "roofline": {"kernel": "kt_weighted_reduce (kt_reduce_kernel, K=%d, %s)" % (w.K, w.dtype),
                      "bound": "hbm", "achieved": round(res["reduce_GBps"], 2), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(res["reduce_GBps"] / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(w.name), "traffic_unit": "bytes per launch"},
+                     "traffic": measured_traffic(w.name), "traffic_unit": "bytes per launch",
+                     "traffic_source": "profiles/kt_kernels_%s.txt (FETCH_SIZE / WRITE_SIZE counter runs of this "
+                                       "command, not of this run; null once the kernel sources have changed)" % w.name},
         "memory_system": ceil,
         "cpu_baseline": cpu,
         "also": also,
