@@ -326,6 +326,36 @@ kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
                                float momentum, float weight_decay,
                                int first_step, void *stream);
 
+/*
+ * kt_fused_step for callers that cannot allocate device memory: code that runs
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same kernels and bit-identical results, but the
+ * plan's tables and the call's pointer table live in a device array of fixed
+ * size that is part of the library's code object (one copy per GPU, held until
+ * the process ends) instead of in memory the library allocates.  The call
+ * allocates and frees nothing on the device and creates no events.
+ *
+ * Limits: tables (16 bytes per 16 KiB tile, 16 per tensor, 8 per bucket) plus
+ * the pointer table must fit 4 MiB, and the pointer table (2 T + (K-1) *
+ * num_buckets entries) 65536 entries; devices 0..15.  Beyond that the call
+ * returns KT_EUNSUPPORTED and does nothing.
+ *
+ * All calls on one GPU share the array.  It keeps the tables of the last call:
+ * a call with the same plan and the same pointers uploads nothing and only
+ * enqueues its kernel (such a call may be recorded under stream capture); any
+ * other call copies its tables into the array on `stream`, ordered behind the
+ * work already enqueued there, and waits for those copies to finish before it
+ * returns.  Calls that overlap in time on one GPU (different streams or
+ * threads, or a graph replay of an earlier call against a new call) with
+ * different plans or pointers race on the array: serialise them.  Nothing in
+ * the array needs to start at zero.
+ */
+kt_status kt_fused_step_noalloc(kt_plan *plan, int bucket,
+                                const void *const *local_tensor_ptrs,
+                                const void *const *peer_bufs, int K,
+                                const float *weights, float scale,
+                                void *const *out_tensor_ptrs, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
+        L.kt_fused_step_noalloc.argtypes = L.kt_fused_step.argtypes
+        L.kt_fused_step_noalloc.restype = i32
         for n in ("kt_plan_shares", "kt_plan_create", "kt_plan_destroy", "kt_plan_bucket_info",
                   "kt_plan_tensor_info", "kt_bucket_pack", "kt_weighted_reduce", "kt_bucket_unpack_scale",
                   "kt_plan_num_buckets", "kt_plan_num_tensors"):
@@ -280,6 +282,12 @@ class Plan:
                       stream=None):
         """peer_bufs: flat sequence over peers 1..K-1, entry [b * (K-1) + (k-1)]."""
         self._fused(lib().kt_fused_step, bucket, local_tensors, peer_bufs, K, weights, scale, out_tensors, stream)
+
+    def kt_fused_step_noalloc(self, bucket: int, local_tensors, peer_bufs, K: int, weights, scale: float,
+                              out_tensors, stream=None):
+        """kt_fused_step through the entry point that allocates nothing."""
+        self._fused(lib().kt_fused_step_noalloc, bucket, local_tensors, peer_bufs, K, weights, scale, out_tensors,
+                    stream)
 
     def kt_bucket_unpack_sgd(self, bucket: int, bucket_bufs, scale: float, params, momenta, lr: float,
                              momentum: float, weight_decay: float, first_step: bool, stream=None):

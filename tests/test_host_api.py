@@ -352,6 +352,7 @@ def test_binding_rejects_arrays_of_the_wrong_length():
         lambda: p.kt_weighted_reduce(-1, b3 + b3, 2, [0.5, 0.5], b3[:2], stream=0),
         lambda: p.kt_fused_step(-1, t3, b3[:2], 2, [0.5, 0.5], 1.0, t3, stream=0),
         lambda: p.kt_fused_step(-1, t3[:2], b3, 2, [0.5, 0.5], 1.0, t3, stream=0),
+        lambda: p.kt_fused_step_noalloc(-1, t3, b3, 2, [0.5, 0.5], 1.0, t3[:1], stream=0),
         lambda: p.kt_bucket_unpack_sgd(-1, b3, 1.0, t3, t3[:2], 0.1, 0.9, 0.0, True, stream=0),
         lambda: p.kt_bucket_unpack_sgd(-1, b3[:1], 1.0, t3, t3, 0.1, 0.9, 0.0, True, stream=0),
         lambda: p.kt_bucket_pack(-1, p.marshal(t3[:2]), p.marshal(b3), stream=0),     # pre-marshalled arrays too
@@ -359,3 +360,26 @@ def test_binding_rejects_arrays_of_the_wrong_length():
     for fn in bad:
         with pytest.raises(ValueError):
             fn()
+
+
+def test_noalloc_limits_and_argument_errors_without_gpu():
+    """The entry point that allocates nothing rejects plans beyond its fixed
+    table space, and bad arguments, on the host before any GPU call."""
+    big = kt.Plan([1 << 31], "f32", 0, 16)                  # 2^19 tiles: 8 MiB of tile table
+    with pytest.raises(kt.KtError) as ei:
+        big.kt_fused_step_noalloc(-1, [4096], [], 1, [1.0], 1.0, [1 << 40], stream=0)
+    assert ei.value.status_name == "KT_EUNSUPPORTED" and "at most" in str(ei.value)
+    many = kt.Plan([4] * 40000, "f32", 0, 16)               # 80 000 pointers
+    with pytest.raises(kt.KtError) as ei:
+        many.kt_fused_step_noalloc(-1, [4096 + 16 * i for i in range(40000)], [], 1, [1.0], 1.0,
+                                   [(1 << 30) + 16 * i for i in range(40000)], stream=0)
+    assert ei.value.status_name == "KT_EUNSUPPORTED"
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    for fn, want in ((lambda: p.kt_fused_step_noalloc(-1, [16, 1600], [4096], 0, [], 1.0, [32000, 48000], stream=0), "KT_EINVAL"),
+                     (lambda: p.kt_fused_step_noalloc(-1, [16, 1600], [4098], 2, [1.0, 1.0], 1.0, [32000, 48000], stream=0), "KT_EALIGN"),
+                     (lambda: p.kt_fused_step_noalloc(-1, [16, 1600], [4096], 2, [1.0, 1.0], 1.0, [4100, 48000], stream=0), "KT_EINVAL")):
+        with pytest.raises(kt.KtError) as ei:
+            fn()
+        assert ei.value.status_name == want, str(ei.value)
+    # nothing to do: returns before any GPU is touched
+    kt.Plan([], "f32", 0, 16).kt_fused_step_noalloc(-1, [], [], 1, [1.0], 1.0, [], stream=0)

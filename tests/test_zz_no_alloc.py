@@ -1,0 +1,131 @@
+"""GPU test of kt_fused_step_noalloc, the entry point for callers that cannot
+allocate device memory: through the C ABI, against kt_fused_step on the same
+inputs (same kernels, so bit-identical) and against the CPU checker's
+un-bucketed definition, on two calls in a row, the second with a smaller
+input, then a repeat that finds its tables already in place."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2505_10183_amd as kt
+from paper_2505_10183_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(autouse=True)
+def announce(request):
+    print("\n[gpu-case] %s" % request.node.nodeid, file=sys.stderr, flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+def host(t):
+    return wl.to_host_array(t)
+
+
+def raw(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+class Case:
+    """One gradient set with its peers packed, outputs for both entry points."""
+
+    def __init__(self, w, scale):
+        self.w, self.scale = w, scale
+        K, dtype = w.K, w.dtype
+        td = wl.torch_dtype(dtype)
+        self.plan_ref = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+        self.plan_na = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)   # never makes an allocating call
+        nb = self.plan_ref.num_buckets
+        _, self.weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
+        self.wts = oracle.share_weights(oracle.plan_shares(w.throughputs, w.global_batch), w.global_batch)
+        self.grads = [wl.gradient_set(w, k, DEV) for k in range(K)]
+        peers = [[torch.empty(n, dtype=td, device=DEV) for n in self.plan_ref.bucket_elems()] for _ in range(K)]
+        for k in range(1, K):
+            self.plan_ref.kt_bucket_pack(-1, self.grads[k], peers[k])
+        self.others = [peers[k][b] for b in range(nb) for k in range(1, K)]
+        self.keep = peers
+        self.out_ref = [torch.full_like(t, 3.0) for t in self.grads[0]]
+        self.out_na = [torch.full_like(t, 5.0) for t in self.grads[0]]
+        self.plan_ref.kt_fused_step(-1, self.grads[0], self.others, K, self.weights, scale, self.out_ref)
+        torch.cuda.synchronize()
+
+    def call(self, stream=None):
+        self.plan_na.kt_fused_step_noalloc(-1, self.grads[0], self.others, self.w.K, self.weights, self.scale,
+                                           self.out_na, stream=stream)
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        hg = [[host(t) for t in g] for g in self.grads]
+        want = oracle.direct(hg, self.wts, self.scale, self.w.dtype, "S")
+        for t in range(len(self.w.numels)):
+            got = host(self.out_na[t])
+            assert raw(got).tobytes() == raw(host(self.out_ref[t])).tobytes(), (what, "vs kt_fused_step", t)
+            assert raw(got).tobytes() == raw(want[t]).tobytes(), (what, "vs checker", t)
+
+    def reset(self):
+        for t in self.out_na:
+            t.fill_(5.0)
+        torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_noalloc_matches_fused_step_on_two_calls_in_a_row(dtype):
+    big = Case(wl.ragged_workload(dtype=dtype, K=4, seed=61, n_tensors=40), 0.37)
+    small = Case(wl.ragged_workload(dtype=dtype, K=3, seed=62, n_tensors=24, cap_bytes=64 * 1024), 1.0)
+    assert sum(small.w.numels) < sum(big.w.numels) and small.plan_na.num_tiles < big.plan_na.num_tiles
+    # the library's code object (which holds the fixed device array) is loaded by the first call
+    warm = Case(wl.ragged_workload(dtype=dtype, K=2, seed=63, n_tensors=24), 1.0)
+    warm.call()
+    warm.check("warm-up")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        torch.zeros(8, device=DEV).add_(1)          # the stream exists on the device before memory is measured
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+
+    big.call()
+    small.call()                       # smaller input: shorter tables over the previous call's
+    big.check("first call")
+    small.check("second call (smaller)")
+
+    small.reset()
+    small.call()                       # same plan, same pointers: nothing is uploaded
+    small.check("repeat")
+
+    big.reset()
+    with torch.cuda.stream(side):
+        big.call(stream=side)          # back to the larger input, on another stream
+    side.synchronize()
+    big.check("larger again, side stream")
+
+    assert torch.cuda.mem_get_info()[0] == free_before, "device memory was allocated"
+
+
+def test_noalloc_recorded_into_a_graph_after_an_eager_call():
+    c = Case(wl.ragged_workload(dtype="f32", K=3, seed=64, n_tensors=30), 0.5)
+    c.call()
+    c.check("eager")
+    c.reset()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        c.call()
+    for i in range(3):
+        c.reset()
+        g.replay()
+        c.check("replay %d" % i)
+    # a call whose tables are not in the array cannot be recorded
+    other = Case(wl.ragged_workload(dtype="f32", K=2, seed=65, n_tensors=26), 1.0)
+    g2 = torch.cuda.CUDAGraph()
+    with pytest.raises(kt.KtError) as ei:
+        with torch.cuda.graph(g2):
+            other.call()
+    assert ei.value.status_name == "KT_EUNSUPPORTED"
+    torch.cuda.synchronize()
+    other.call()
+    other.check("eager after the refused capture")
