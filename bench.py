@@ -101,7 +101,13 @@ def step(st, scale=1.0, ev=None):
         ev[3].record()
 
 
-def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
+def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, events_in_timed_loop=True):
+    """Times `steps` chained steps (wall clock, synchronised on both sides) and, with events
+    on the launch stream, the reduce inside the step and every step on its own.  The events
+    are recorded inside the timed loop for the headline workload (`events_in_timed_loop`);
+    for the small launch-bound sets, where four event records per step would themselves
+    cost a third of the step, the wall-clock loop runs without them and a second loop
+    carries the events."""
     import torch
     st = setup(name, dev, in_place, misalign)
     w = st["w"]
@@ -112,10 +118,14 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        step(st, ev=evs[i])
+        step(st, ev=evs[i] if events_in_timed_loop else None)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_step = (t1 - t0) * 1e3 / steps
+    if not events_in_timed_loop:
+        for i in range(steps):
+            step(st, ev=evs[i])
+        torch.cuda.synchronize()
     ms_reduce = sum(e[1].elapsed_time(e[2]) for e in evs) / steps
     per_step = sorted(e[0].elapsed_time(e[3]) for e in evs)
     per_reduce = sorted(e[1].elapsed_time(e[2]) for e in evs)
@@ -190,6 +200,11 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False):
         res.update({"graph_step_ms": ms_graph, "graph_step_GBps": (K + 5) * s * e / (ms_graph * 1e-3) / 1e9,
                     "graph_buckets_per_s": st["nb"] / (ms_graph * 1e-3)})
     return res, st
+
+
+def wl_total(name):
+    from paper_2505_10183_amd import workloads as wl
+    return wl.WORKLOADS[name].total_elems
 
 
 def host_threads():
@@ -328,6 +343,113 @@ def ceilings(dev, reps=10):
     return res
 
 
+def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
+    """Interleaved comparison of library builds (paper_2505_10183_amd/build.py --out ... -D...)
+    in ONE process on ONE set of device buffers: every round times every kernel on every
+    build in turn, so that machine drift (a few per cent between runs and boxes) hits all
+    builds alike.  Prints one line per (kernel, build): median and best of the per-round
+    means, in GB/s of algorithmic bytes.  Also times the same kernels with the gradient /
+    parameter tensors laid out as views into flat buffers with the bucket layout
+    (`*_views`: their addresses are then congruent with the bucket's 16 KiB tiles) and the
+    chained step launched bucket by bucket instead of batched (`step_per_bucket`)."""
+    import statistics
+    import torch
+    import paper_2505_10183_amd as kt
+    from paper_2505_10183_amd import binding
+
+    st = setup(workload, dev)
+    w, K, nb = st["w"], st["K"], st["nb"]
+    e, s = w.total_elems, w.elem_size
+    libs, plans = {}, {}
+    for name, path in variants:
+        binding._lib = None
+        binding.LIB_PATH = os.path.abspath(path)
+        libs[name] = binding.lib()
+        plans[name] = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+    td = st["local"][0].dtype
+    elems = st["plan"].bucket_elems()
+    flat_l = [torch.empty(n, dtype=td, device=dev).normal_(0, w.sigma) for n in elems]
+    flat_o = [torch.empty(n, dtype=td, device=dev) for n in elems]
+    flat_p = [torch.zeros(n, dtype=torch.float32, device=dev) for n in elems]
+    flat_v = [torch.zeros(n, dtype=torch.float32, device=dev) for n in elems]
+    view_l, view_o, view_p, view_v = [], [], [], []
+    for t, n in enumerate(w.numels):
+        b, off = st["plan"].tensor_info(t)
+        view_l.append(flat_l[b][off:off + n])
+        view_o.append(flat_o[b][off:off + n])
+        view_p.append(flat_p[b][off:off + n])
+        view_v.append(flat_v[b][off:off + n])
+    params = [torch.zeros(n, dtype=torch.float32, device=dev) for n in w.numels]
+    moms = [torch.zeros(n, dtype=torch.float32, device=dev) for n in w.numels]
+    m = st["plan"].marshal
+    a_vl, a_vo, a_vp, a_vv, a_p, a_v = m(view_l), m(view_o), m(view_p), m(view_v), m(params), m(moms)
+    a_l, a_s0, a_pe, a_ot, a_o, a_r, a_w = (st["a_local"], st["a_slot0"], st["a_peers"], st["a_others"], st["a_outs"],
+                                            st["a_result"], st["a_w"])
+
+    def table(p):
+        def per_bucket():
+            for b in range(nb):
+                p.kt_bucket_pack(b, a_l, a_s0)
+                p.kt_weighted_reduce(b, a_pe, K, a_w, a_o)
+                p.kt_bucket_unpack_scale(b, a_o, 1.0, a_r)
+
+        def batched():
+            p.kt_bucket_pack(-1, a_l, a_s0)
+            p.kt_weighted_reduce(-1, a_pe, K, a_w, a_o)
+            p.kt_bucket_unpack_scale(-1, a_o, 1.0, a_r)
+        return {
+            "pack": (lambda: p.kt_bucket_pack(-1, a_l, a_s0), 2 * s),
+            "pack_views": (lambda: p.kt_bucket_pack(-1, a_vl, a_s0), 2 * s),
+            "reduce": (lambda: p.kt_weighted_reduce(-1, a_pe, K, a_w, a_o), (K + 1) * s),
+            "unpack": (lambda: p.kt_bucket_unpack_scale(-1, a_o, 1.0, a_r), 2 * s),
+            "unpack_views": (lambda: p.kt_bucket_unpack_scale(-1, a_o, 1.0, a_vo), 2 * s),
+            "step": (batched, (K + 5) * s),
+            "step_per_bucket": (per_bucket, (K + 5) * s),
+            "fused": (lambda: p.kt_fused_step(-1, a_l, a_ot, K, a_w, 1.0, a_r), (K + 1) * s),
+            "fused_scale037": (lambda: p.kt_fused_step(-1, a_l, a_ot, K, a_w, 0.37, a_r), (K + 1) * s),
+            "fused_inplace": (lambda: p.kt_fused_step(-1, a_l, a_ot, K, a_w, 1.0, a_l), (K + 1) * s),
+            "fused_views": (lambda: p.kt_fused_step(-1, a_vl, a_ot, K, a_w, 1.0, a_vo), (K + 1) * s),
+            "fused_views_inplace": (lambda: p.kt_fused_step(-1, a_vl, a_ot, K, a_w, 1.0, a_vl), (K + 1) * s),
+            "sgd": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False), s + 16),
+            "sgd_views": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_vp, a_vv, 0.1, 0.9, 5e-4, False), s + 16),
+        }
+
+    def timeit(fn):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
+        fn()
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    res = {(v, k): [] for v, _ in variants for k in kernel_names}
+    for _ in range(rounds):
+        for k in kernel_names:
+            for v, _ in variants:
+                binding._lib = libs[v]
+                res[(v, k)].append(timeit(table(plans[v])[k][0]))
+    print("# %s: %d elements %s, K=%d, %d buckets; %d rounds x %d launches per (kernel, build), interleaved"
+          % (w.name, e, w.dtype, K, nb, rounds, reps))
+    print("# %-20s %-12s %10s %9s %7s %10s %9s" % ("kernel", "build", "median_ms", "GB/s", "% peak", "best_ms", "GB/s"))
+    for k in kernel_names:
+        bpe = table(plans[variants[0][0]])[k][1]
+        for v, _ in variants:
+            t = res[(v, k)]
+            med, mn = statistics.median(t), min(t)
+            print("  %-20s %-12s %10.4f %9.1f %7.1f %10.4f %9.1f"
+                  % (k, v, med, bpe * e / med / 1e6, bpe * e / med / 1e6 / (HBM_PEAK_GBS / 100), mn, bpe * e / mn / 1e6))
+    sys.stdout.flush()
+    for v, _ in variants:
+        binding._lib = libs[v]
+        plans[v].close()
+    binding._lib = libs[variants[0][0]]
+    st["plan"].close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -346,6 +468,13 @@ def main():
     ap.add_argument("--misalign", action="store_true",
                     help="offset every bucket buffer by one element: the library then takes its "
                          "element-wise (4-byte / 2-byte) kernels instead of the 16-byte ones")
+    ap.add_argument("--ab", default="", help="interleaved comparison of library builds: comma list of name=path "
+                                             "(see ab_compare); prints a table instead of the JSON line")
+    ap.add_argument("--kernels", default="reduce,fused,sgd", help="kernels compared by --ab")
+    ap.add_argument("--rounds", type=int, default=5, help="rounds of --ab")
+    ap.add_argument("--ceilings-only", action="store_true",
+                    help="run only the memory-system probes on flat 1 GiB buffers and print their JSON "
+                         "(the command the counter summaries under profiles/ are taken with)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -364,6 +493,11 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
+    if args.ab:
+        variants = [tuple(x.split("=", 1)) for x in args.ab.split(",") if x]
+        ab_compare(args.workload, [k for k in args.kernels.split(",") if k], variants, dev,
+                   rounds=args.rounds, reps=10)
+        return
     if args.calibrate:
         a = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
         b = torch.empty_like(a)
@@ -373,6 +507,9 @@ def main():
         del a, b
         torch.cuda.empty_cache()
 
+    if args.ceilings_only:
+        print(json.dumps({"memory_system": ceilings(dev)}))
+        return
     res, st = time_workload(args.workload, args.steps, args.warmup, dev, not args.out_of_place, args.misalign)
     w = st["w"]
     cpu = None
@@ -387,7 +524,8 @@ def main():
     torch.cuda.empty_cache()
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         try:
-            r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place, args.misalign)
+            r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place, args.misalign,
+                                  events_in_timed_loop=wl_total(name) >= 50_000_000)
             also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
             del s2
         except Exception as exc:                 # noqa: BLE001

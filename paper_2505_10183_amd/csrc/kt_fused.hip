@@ -12,43 +12,68 @@ namespace {
 
 // Mixed tile of the fused pass: per vector, peer 0 comes from the owning tensor
 // (tv.ptr = local gradients), the result goes to the same position of tv.ptr2.
+// Vectors are taken MB at a time per lane, in two phases, so that the loads of
+// all of them are in flight together: (1) find each vector's owner in the staged
+// table and issue its K loads, (2) combine and store; vectors that are not
+// wholly inside one tensor at 16-byte aligned addresses go element by element.
 template <typename T, int K, typename V>
 __device__ __forceinline__ void fused_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n,
                                             const T *const *x, const float *w, float scale)
 {
     constexpr int VE = Elem<T>::VE;
+    constexpr int MB = K <= 4 ? 4 : 2;
     const int nvec = (int)((g.end - g.start + VE - 1) / VE);
 #pragma unroll 1
-    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
-        const int64_t e0 = g.start + (int64_t)v * VE;
-        int i = find_owner_v(tv, nt, e0);
-        if (i >= 0 && e0 + VE <= b_n) {
-            const int64_t r = e0 - tv.off[i];
-            if (r + VE <= tv.numel[i]) {
-                const uintptr_t ps = tv.ptr[i] + (uintptr_t)r * sizeof(T);
-                const uintptr_t pd = tv.ptr2[i] + (uintptr_t)r * sizeof(T);
-                if (((ps | pd) & 15u) == 0) {
-                    Acc<T> acc;
-                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), w[0]);
+    for (int v0 = threadIdx.x; v0 < nvec; v0 += MB * KT_BLOCK) {
+        u32x4 r[MB][K];
+        uintptr_t where[MB];      // destination of a whole vector; 0 = none, 1 = element-wise
 #pragma unroll
-                    for (int k = 1; k < K; ++k)
-                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v), w[k]);
-                    st_vec(reinterpret_cast<void *>(pd), scale_vec<T>(acc.finish(), scale));
-                    continue;
+        for (int j = 0; j < MB; ++j) {
+            const int v = v0 + j * KT_BLOCK;
+            where[j] = 0;
+            if (v < nvec) {
+                where[j] = 1;
+                const int64_t e0 = g.start + (int64_t)v * VE;
+                const int i = find_owner_v(tv, nt, e0);
+                if (i >= 0 && e0 + VE <= b_n) {
+                    const int64_t rr = e0 - tv.off[i];
+                    if (rr + VE <= tv.numel[i]) {
+                        const uintptr_t ps = tv.ptr[i] + (uintptr_t)rr * sizeof(T);
+                        const uintptr_t pd = tv.ptr2[i] + (uintptr_t)rr * sizeof(T);
+                        if (((ps | pd) & 15u) == 0) {
+                            r[j][0] = ld_vec(reinterpret_cast<const void *>(ps));
+#pragma unroll
+                            for (int k = 1; k < K; ++k) r[j][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v);
+                            where[j] = pd;
+                        }
+                    }
                 }
             }
         }
-#pragma unroll 1
-        for (int q = 0; q < VE; ++q) {
-            const int64_t e = e0 + q;
-            if (e >= b_n) break;
-            while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
-            if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
-                const int64_t r = e - tv.off[i];
-                float a = __fmul_rn(w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
 #pragma unroll
-                for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k - 1] + (e - g.start))), a);
-                st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
+        for (int j = 0; j < MB; ++j) {
+            if (where[j] > 1) {
+                Acc<T> acc;
+                acc.first(r[j][0], w[0]);
+#pragma unroll
+                for (int k = 1; k < K; ++k) acc.add(r[j][k], w[k]);
+                st_vec(reinterpret_cast<void *>(where[j]), scale_vec<T>(acc.finish(), scale));
+            } else if (where[j] == 1) {
+                const int64_t e0 = g.start + (int64_t)(v0 + j * KT_BLOCK) * VE;
+                int i = find_owner_v(tv, nt, e0);
+#pragma unroll 1
+                for (int q = 0; q < VE; ++q) {
+                    const int64_t e = e0 + q;
+                    if (e >= b_n) break;
+                    while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+                    if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
+                        const int64_t rr = e - tv.off[i];
+                        float a = __fmul_rn(w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + rr)));
+#pragma unroll
+                        for (int k = 1; k < K; ++k) a = __fmaf_rn(w[k], widen(ld_elem(x[k - 1] + (e - g.start))), a);
+                        st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + rr, scale_elem(narrow<T>(a), scale));
+                    }
+                }
             }
         }
     }

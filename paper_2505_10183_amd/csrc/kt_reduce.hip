@@ -2,10 +2,20 @@
 // element); nothing here is a contraction, so no MFMA.
 #include "kt_device.h"
 
+// Occupancy the compiler must reach for the main kernel (waves per SIMD); 0 leaves it alone.
+#ifndef KT_REDUCE_WAVES
+#define KT_REDUCE_WAVES 0
+#endif
+#if KT_REDUCE_WAVES > 0
+#define KT_REDUCE_OCC __attribute__((amdgpu_waves_per_eu(KT_REDUCE_WAVES, KT_REDUCE_WAVES)))
+#else
+#define KT_REDUCE_OCC
+#endif
+
 namespace {
 
 template <typename T, int K>
-__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
+__global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
                                                              const void *const *peer_ptrs, KtWeights wts,
                                                              void *const *out_ptrs)
 {

@@ -94,13 +94,13 @@ template <> struct SgdVec<uint16_t> {
 // Mixed tile: tv.ptr = parameters, tv.ptr2 = momentum of the owning tensor.
 template <typename T, typename V>
 __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, const T *src,
-                                          const KtSgd &a, int vec_ok)
+                                          const KtSgd &a, int vec_ok, int part, int parts)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int PV = SgdVec<T>::PV;
     const int nvec = (int)((g.end - g.start + VE - 1) / VE);
 #pragma unroll 1
-    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+    for (int v = part * KT_BLOCK + threadIdx.x; v < nvec; v += parts * KT_BLOCK) {
         const int64_t e0 = g.start + (int64_t)v * VE;
         int i = find_owner_v(tv, nt, e0);
         if (vec_ok && i >= 0 && e0 + VE <= b_n) {
@@ -144,6 +144,133 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
     }
 }
 
+// A tile of the bucket (16 KiB of gradient) goes with 16 KiB (fp32) or 32 KiB
+// (bf16) each of parameters and momentum, read and written.  SPLIT workgroups
+// share one tile so that every workgroup, whatever the gradient type, has
+// KT_SGD_QB quads of 4 elements per lane, all loaded before the first store.
+#ifndef KT_SGD_QB
+#define KT_SGD_QB 4
+#endif
+
+template <typename T> struct SgdShape {
+    static constexpr int QPT = (int)(KT_TILE_VECS * Elem<T>::VE / 4 / KT_BLOCK);   // quads per lane in a full tile
+    static constexpr int QB = QPT < KT_SGD_QB ? QPT : KT_SGD_QB;                    // quads per lane and workgroup
+    static constexpr int SPLIT = QPT / QB;                                          // workgroups per tile
+    static_assert(QPT % QB == 0, "quads per lane");
+};
+
+// A full solid tile's share of one workgroup: QB quads per lane, every load
+// issued before the first store.
+template <typename T>
+__device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x4 *v4, int part, const KtSgd &a)
+{
+    constexpr int QB = SgdShape<T>::QB;
+    const int tid = threadIdx.x;
+    const Quad<T> *s4 = reinterpret_cast<const Quad<T> *>(src_tile);
+    const int u0 = part * QB;
+    Quad<T> gr[QB];
+    u32x4 pr[QB], vr[QB];
+#pragma unroll
+    for (int u = 0; u < QB; ++u) {
+        const int idx = (u0 + u) * KT_BLOCK + tid;
+        gr[u] = ld_quad(s4 + idx);
+        pr[u] = ld_vec(p4 + idx);
+        vr[u] = u32x4{0, 0, 0, 0};
+        if (!a.first) vr[u] = ld_vec(v4 + idx);
+    }
+#pragma unroll
+    for (int u = 0; u < QB; ++u) {
+        const int idx = (u0 + u) * KT_BLOCK + tid;
+        sgd_quad(gr[u], pr[u], vr[u], a);
+        st_vec(p4 + idx, pr[u]);
+        st_vec(v4 + idx, vr[u]);
+    }
+}
+
+#ifndef KT_SGD_BF16_MODE
+#define KT_SGD_BF16_MODE 0
+#endif
+#if KT_SGD_BF16_MODE == 1
+// bf16, 16-byte gradient loads: a lane takes 8 consecutive elements, i.e. two
+// consecutive 16-byte vectors of p and of v (32 contiguous bytes per lane).
+template <>
+__device__ __forceinline__ void sgd_full_tile<uint16_t>(const uint16_t *src_tile, u32x4 *p4, u32x4 *v4, int part,
+                                                        const KtSgd &a)
+{
+    constexpr int VB = SgdShape<uint16_t>::QB / 2;
+    static_assert(SgdShape<uint16_t>::QB % 2 == 0, "pairs of quads");
+    const int tid = threadIdx.x;
+    const u32x4 *s16 = reinterpret_cast<const u32x4 *>(src_tile);
+    u32x4 gr[VB], pr[VB][2], vr[VB][2];
+#pragma unroll
+    for (int j = 0; j < VB; ++j) {
+        const int vi = (part * VB + j) * KT_BLOCK + tid;
+        gr[j] = ld_vec(s16 + vi);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            pr[j][h] = ld_vec(p4 + 2 * vi + h);
+            vr[j][h] = u32x4{0, 0, 0, 0};
+            if (!a.first) vr[j][h] = ld_vec(v4 + 2 * vi + h);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < VB; ++j) {
+        const int vi = (part * VB + j) * KT_BLOCK + tid;
+        SgdVec<uint16_t>::apply(gr[j], pr[j], vr[j], a);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            st_vec(p4 + 2 * vi + h, pr[j][h]);
+            st_vec(v4 + 2 * vi + h, vr[j][h]);
+        }
+    }
+}
+#elif KT_SGD_BF16_MODE == 2
+// bf16, 16-byte gradient loads with every access of a wavefront contiguous: a
+// wavefront takes 512 consecutive elements, lane l loads gradient elements
+// [8l, 8l+8) and the parameter / momentum quads [4l, 4l+4) and [256+4l, 256+4l+4);
+// the gradient halves travel to the lanes that hold their parameters through
+// the cross-lane permute (no memory involved).
+template <>
+__device__ __forceinline__ void sgd_full_tile<uint16_t>(const uint16_t *src_tile, u32x4 *p4, u32x4 *v4, int part,
+                                                        const KtSgd &a)
+{
+    constexpr int VB = SgdShape<uint16_t>::QB / 2;
+    static_assert(SgdShape<uint16_t>::QB % 2 == 0, "pairs of quads");
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const u32x4 *s16 = reinterpret_cast<const u32x4 *>(src_tile);
+    u32x4 gr[VB], pr[VB][2], vr[VB][2];
+#pragma unroll
+    for (int j = 0; j < VB; ++j) {
+        const int base = ((part * VB + j) * (KT_BLOCK / 64) + wave) * 64;   // first gradient vector of the wavefront
+        gr[j] = ld_vec(s16 + base + lane);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            pr[j][h] = ld_vec(p4 + 2 * base + 64 * h + lane);
+            vr[j][h] = u32x4{0, 0, 0, 0};
+            if (!a.first) vr[j][h] = ld_vec(v4 + 2 * base + 64 * h + lane);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < VB; ++j) {
+        const int base = ((part * VB + j) * (KT_BLOCK / 64) + wave) * 64;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            // the quad [256h + 4l, +4) is half (l & 1) of the vector that lane 32h + l/2 loaded
+            const int from = (32 * h + (lane >> 1)) * 4;
+            uint32_t b[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) b[d] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)gr[j][d]);
+            Quad<uint16_t> q;
+            q.d[0] = (lane & 1) ? b[2] : b[0];
+            q.d[1] = (lane & 1) ? b[3] : b[1];
+            sgd_quad(q, pr[j][h], vr[j][h], a);
+            st_vec(p4 + 2 * base + 64 * h + lane, pr[j][h]);
+            st_vec(v4 + 2 * base + 64 * h + lane, vr[j][h]);
+        }
+    }
+}
+#endif
+
 template <typename T>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *bucket_ptrs,
@@ -152,9 +279,11 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int QPT = SgdShape<T>::QPT, SPLIT = SgdShape<T>::SPLIT;
     __shared__ LdsTable lds;
 
-    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const int part = SPLIT == 1 ? 0 : (int)(blockIdx.x % SPLIT);
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x / SPLIT];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const T *src = reinterpret_cast<const T *>(bucket_ptrs[g.bucket]);
     const int tid = threadIdx.x;
@@ -167,37 +296,15 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
         float *pp = reinterpret_cast<float *>(param_ptrs[tl.t0]) + rel;
         float *vp = reinterpret_cast<float *>(mom_ptrs[tl.t0]) + rel;
         if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0) {
-            constexpr int QPT = (int)(TILE_ELEMS / 4 / KT_BLOCK);     // quads per lane in a full tile
             const Quad<T> *s4 = reinterpret_cast<const Quad<T> *>(src + g.start);
             u32x4 *p4 = reinterpret_cast<u32x4 *>(pp);
             u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
             const int nq = (int)((g.end - g.start) / 4);
             if (nq == QPT * KT_BLOCK) {
-                constexpr int QB = QPT < 4 ? QPT : 4;     // quads in flight per lane
-                static_assert(QPT % QB == 0, "quads per lane");
-#pragma unroll 1
-                for (int u0 = 0; u0 < QPT; u0 += QB) {
-                    Quad<T> gr[QB];
-                    u32x4 pr[QB], vr[QB];
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        const int idx = (u0 + u) * KT_BLOCK + tid;
-                        gr[u] = ld_quad(s4 + idx);
-                        pr[u] = ld_vec(p4 + idx);
-                        vr[u] = u32x4{0, 0, 0, 0};
-                        if (!a.first) vr[u] = ld_vec(v4 + idx);
-                    }
-#pragma unroll
-                    for (int u = 0; u < QB; ++u) {
-                        const int idx = (u0 + u) * KT_BLOCK + tid;
-                        sgd_quad(gr[u], pr[u], vr[u], a);
-                        st_vec(p4 + idx, pr[u]);
-                        st_vec(v4 + idx, vr[u]);
-                    }
-                }
+                sgd_full_tile<T>(src + g.start, p4, v4, part, a);
             } else {
 #pragma unroll 1
-                for (int idx = tid; idx < nq; idx += KT_BLOCK) {
+                for (int idx = part * KT_BLOCK + tid; idx < nq; idx += SPLIT * KT_BLOCK) {
                     const Quad<T> gq = ld_quad(s4 + idx);
                     u32x4 pr = ld_vec(p4 + idx), vr = u32x4{0, 0, 0, 0};
                     if (!a.first) vr = ld_vec(v4 + idx);
@@ -216,10 +323,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
     const void *const *mp = reinterpret_cast<const void *const *>(mom_ptrs);
     if (nt <= KT_LDS_TENSORS) {
         const LdsView tv = stage_lds(lds, tb, pp, mp, tl.t0, nt);
-        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT);
     } else {
         const GlobalView tv = global_view(tb, pp, mp, tl.t0);
-        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok);
+        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT);
     }
 }
 
@@ -230,10 +337,15 @@ int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, i
                          const KtSgd &a, bool vector_ok, void *stream)
 {
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    dim3 grid((unsigned)ntiles), block(KT_BLOCK);
+    dim3 block(KT_BLOCK);
+    // a grid may not hold 2^32 or more lanes
+    const int split = dt == KT_F32 ? SgdShape<float>::SPLIT : SgdShape<uint16_t>::SPLIT;
+    if (ntiles * split * KT_BLOCK >= ((int64_t)1 << 32)) return (int)hipErrorInvalidConfiguration;
     if (dt == KT_F32)
-        kt_unpack_sgd_kernel<float><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+        kt_unpack_sgd_kernel<float><<<dim3((unsigned)(ntiles * SgdShape<float>::SPLIT)), block, 0, s>>>(
+            tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
     else
-        kt_unpack_sgd_kernel<uint16_t><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+        kt_unpack_sgd_kernel<uint16_t><<<dim3((unsigned)(ntiles * SgdShape<uint16_t>::SPLIT)), block, 0, s>>>(
+            tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
     return (int)hipGetLastError();
 }
