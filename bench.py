@@ -31,8 +31,8 @@ HBM_PEAK_GBS = 8000.0
 # They describe the kernel sources with the digest below; after any change to those
 # sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip", "kt_sgd.hip")
-TRAFFIC_SOURCES_SHA = "baeea60e5039986d"
-TRAFFIC_BYTES = {"decoder_1p3b": 23704836585, "vit_b16": 3119133706}
+TRAFFIC_SOURCES_SHA = "0b999fe19351a1ee"
+TRAFFIC_BYTES = {"decoder_1p3b": 23704865758, "vit_b16": 3119133916}
 
 
 def measured_traffic(workload):
@@ -46,6 +46,9 @@ def measured_traffic(workload):
     return TRAFFIC_BYTES.get(workload)
 
 
+ALIGN_BYTES = 16      # --align: start of every tensor inside its bucket
+
+
 def setup(name, dev, in_place=True, misalign=False):
     import torch
     import paper_2505_10183_amd as kt
@@ -53,7 +56,7 @@ def setup(name, dev, in_place=True, misalign=False):
 
     w = wl.WORKLOADS[name]
     K = w.K
-    plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+    plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
     shares, weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
     td = wl.torch_dtype(w.dtype)
     nb = plan.num_buckets
@@ -236,7 +239,7 @@ def cpu_baseline(st, budget_elems):
     def fetch(b):
         n, first, cnt = plan.bucket_info(b)
         numels = w.numels[first:first + cnt]
-        lay = oracle.assign_buckets(numels, w.elem_size, 0, 16)
+        lay = oracle.assign_buckets(numels, w.elem_size, 0, ALIGN_BYTES)
         loc = [wl.to_host_array(st["local"][t]) for t in range(first, first + cnt)]
         others = [wl.to_host_array(st["peers"][k][b]) for k in range(1, K)]
         return lay, numels, loc, others
@@ -365,7 +368,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
         binding._lib = None
         binding.LIB_PATH = os.path.abspath(path)
         libs[name] = binding.lib()
-        plans[name] = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+        plans[name] = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
     td = st["local"][0].dtype
     elems = st["plan"].bucket_elems()
     flat_l = [torch.empty(n, dtype=td, device=dev).normal_(0, w.sigma) for n in elems]
@@ -465,6 +468,9 @@ def main():
     ap.add_argument("--no-ceilings", action="store_true", help="skip the memory-system probe")
     ap.add_argument("--lib", default="", help="load this build of libkt.so instead of the in-tree one "
                                               "(variants made with paper_2505_10183_amd/build.py --out)")
+    ap.add_argument("--align", type=int, default=16,
+                    help="align_bytes of the bucket plan (16 as in the workload definitions; 16384 puts every "
+                         "tensor on a tile boundary)")
     ap.add_argument("--misalign", action="store_true",
                     help="offset every bucket buffer by one element: the library then takes its "
                          "element-wise (4-byte / 2-byte) kernels instead of the 16-byte ones")
@@ -483,6 +489,8 @@ def main():
         print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    global ALIGN_BYTES
+    ALIGN_BYTES = args.align
     if args.lib:
         from paper_2505_10183_amd import binding
         binding.LIB_PATH = os.path.abspath(args.lib)
@@ -558,7 +566,8 @@ def main():
                                   res["buckets"], w.bucket_cap_bytes >> 20),
                    "launch": "one batched launch per kernel over all buckets; reduce %s"
                              % ("into its own output buffers" if args.out_of_place else "in place over peer slot 0")
-                             + ("; buckets misaligned by one element (element-wise kernels)" if args.misalign else ""),
+                             + ("; buckets misaligned by one element (element-wise kernels)" if args.misalign else "")
+                             + ("; tensors aligned to %d bytes inside the buckets" % args.align if args.align != 16 else ""),
                    "bytes_per_element": "(K+5)*s = %d" % ((w.K + 5) * w.elem_size)},
         "pct_of_hbm_peak": round(100.0 * res["step_GBps"] / HBM_PEAK_GBS, 2),
         "buckets_per_s": round(res["buckets_per_s"], 1),

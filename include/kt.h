@@ -183,8 +183,11 @@ kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
  *   align_bytes  in      : every tensor starts at a multiple of this inside
  *                          its bucket and the bucket length is rounded up to
  *                          it.  Power of two, multiple of the element size,
- *                          <= 4096.  16 gives the fast vector path; the
- *                          element size gives dense packing.
+ *                          <= 16384.  16 gives the fast vector path; the
+ *                          element size gives dense packing; 16384 (the
+ *                          kernels' tile) makes every tensor start on a tile
+ *                          boundary, so that tensor-side addresses are as
+ *                          well aligned as the tensors' own base addresses.
  *   out          out     : new plan, to be released with kt_plan_destroy.
  * Errors: KT_EINVAL (arguments), KT_ENOMEM, KT_EUNSUPPORTED (the plan would
  * need 2^24 or more 16 KiB tiles, i.e. 256 GiB per peer).

@@ -105,8 +105,8 @@ def plan_shares(thr: Sequence[float], B: int) -> List[int]:
     time_fastest / time_i = thr_i / max thr, and the common factor cancels in
     score_i / sum_j score_j, so throughputs are used directly.
 
-    Reading of "rounded to the nearest integer, ensuring the sum matches":
-    largest remainder.  Take the floor of every quota, then give one extra
+    Reading of the integer-rounding rule stated after the Sec. III-C display
+    equation (which gives no tie or fix-up rule): largest remainder.  Take the floor of every quota, then give one extra
     sample to the R = B - sum floor entries with the largest fractional parts
     (ties to the lowest index).  Whenever plain rounding already sums to B
     this is plain rounding.
@@ -162,7 +162,7 @@ def assign_buckets(numels: Sequence[int], elem_size: int, cap_bytes: int,
     if elem_size not in (2, 4):
         raise ValueError("elem_size")
     if (align_bytes < elem_size or align_bytes % elem_size
-            or align_bytes & (align_bytes - 1) or align_bytes > 4096):
+            or align_bytes & (align_bytes - 1) or align_bytes > 16384):
         raise ValueError("align_bytes")
     if cap_bytes < 0:
         raise ValueError("cap_bytes")
@@ -292,10 +292,9 @@ def bf16_to_f32_array(bits: np.ndarray) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# Load-adaptive sampler partition (Sec. III-C phase 2: "allocates portions of
-# the global mini-batch to each device i based on its score"; Sec. IV-A: the
-# DistributedSampler override that takes per-device scores and distributes
-# dataset indices accordingly)
+# Load-adaptive sampler partition (Sec. III-C phase 2: every device receives a
+# portion of each global mini-batch sized by its score; Sec. IV-A says only
+# that the sampler override splits the dataset indices by the scores)
 # --------------------------------------------------------------------------
 
 _M64 = (1 << 64) - 1

@@ -117,8 +117,8 @@ kt_status kt_build_host_plan(const int64_t *numel, int T, kt_dtype dt, int64_t c
     if (dt != KT_F32 && dt != KT_BF16) { *msg = "unknown dtype"; return KT_EINVAL; }
     if (T < 0 || (T > 0 && !numel)) { *msg = "bad tensor list"; return KT_EINVAL; }
     if (cap_bytes < 0) { *msg = "negative cap_bytes"; return KT_EINVAL; }
-    if (align_bytes < es || align_bytes > 4096 || (align_bytes & (align_bytes - 1)) || align_bytes % es) {
-        *msg = "align_bytes must be a power of two in [element size, 4096]";
+    if (align_bytes < es || align_bytes > KT_TILE_BYTES || (align_bytes & (align_bytes - 1)) || align_bytes % es) {
+        *msg = "align_bytes must be a power of two in [element size, 16384]";
         return KT_EINVAL;
     }
     const int64_t A = align_bytes / es;

@@ -187,90 +187,6 @@ __device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x
     }
 }
 
-#ifndef KT_SGD_BF16_MODE
-#define KT_SGD_BF16_MODE 0
-#endif
-#if KT_SGD_BF16_MODE == 1
-// bf16, 16-byte gradient loads: a lane takes 8 consecutive elements, i.e. two
-// consecutive 16-byte vectors of p and of v (32 contiguous bytes per lane).
-template <>
-__device__ __forceinline__ void sgd_full_tile<uint16_t>(const uint16_t *src_tile, u32x4 *p4, u32x4 *v4, int part,
-                                                        const KtSgd &a)
-{
-    constexpr int VB = SgdShape<uint16_t>::QB / 2;
-    static_assert(SgdShape<uint16_t>::QB % 2 == 0, "pairs of quads");
-    const int tid = threadIdx.x;
-    const u32x4 *s16 = reinterpret_cast<const u32x4 *>(src_tile);
-    u32x4 gr[VB], pr[VB][2], vr[VB][2];
-#pragma unroll
-    for (int j = 0; j < VB; ++j) {
-        const int vi = (part * VB + j) * KT_BLOCK + tid;
-        gr[j] = ld_vec(s16 + vi);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            pr[j][h] = ld_vec(p4 + 2 * vi + h);
-            vr[j][h] = u32x4{0, 0, 0, 0};
-            if (!a.first) vr[j][h] = ld_vec(v4 + 2 * vi + h);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < VB; ++j) {
-        const int vi = (part * VB + j) * KT_BLOCK + tid;
-        SgdVec<uint16_t>::apply(gr[j], pr[j], vr[j], a);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            st_vec(p4 + 2 * vi + h, pr[j][h]);
-            st_vec(v4 + 2 * vi + h, vr[j][h]);
-        }
-    }
-}
-#elif KT_SGD_BF16_MODE == 2
-// bf16, 16-byte gradient loads with every access of a wavefront contiguous: a
-// wavefront takes 512 consecutive elements, lane l loads gradient elements
-// [8l, 8l+8) and the parameter / momentum quads [4l, 4l+4) and [256+4l, 256+4l+4);
-// the gradient halves travel to the lanes that hold their parameters through
-// the cross-lane permute (no memory involved).
-template <>
-__device__ __forceinline__ void sgd_full_tile<uint16_t>(const uint16_t *src_tile, u32x4 *p4, u32x4 *v4, int part,
-                                                        const KtSgd &a)
-{
-    constexpr int VB = SgdShape<uint16_t>::QB / 2;
-    static_assert(SgdShape<uint16_t>::QB % 2 == 0, "pairs of quads");
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const u32x4 *s16 = reinterpret_cast<const u32x4 *>(src_tile);
-    u32x4 gr[VB], pr[VB][2], vr[VB][2];
-#pragma unroll
-    for (int j = 0; j < VB; ++j) {
-        const int base = ((part * VB + j) * (KT_BLOCK / 64) + wave) * 64;   // first gradient vector of the wavefront
-        gr[j] = ld_vec(s16 + base + lane);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            pr[j][h] = ld_vec(p4 + 2 * base + 64 * h + lane);
-            vr[j][h] = u32x4{0, 0, 0, 0};
-            if (!a.first) vr[j][h] = ld_vec(v4 + 2 * base + 64 * h + lane);
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < VB; ++j) {
-        const int base = ((part * VB + j) * (KT_BLOCK / 64) + wave) * 64;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            // the quad [256h + 4l, +4) is half (l & 1) of the vector that lane 32h + l/2 loaded
-            const int from = (32 * h + (lane >> 1)) * 4;
-            uint32_t b[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) b[d] = (uint32_t)__builtin_amdgcn_ds_bpermute(from, (int)gr[j][d]);
-            Quad<uint16_t> q;
-            q.d[0] = (lane & 1) ? b[2] : b[0];
-            q.d[1] = (lane & 1) ? b[3] : b[1];
-            sgd_quad(q, pr[j][h], vr[j][h], a);
-            st_vec(p4 + 2 * base + 64 * h + lane, pr[j][h]);
-            st_vec(v4 + 2 * base + 64 * h + lane, vr[j][h]);
-        }
-    }
-}
-#endif
-
 template <typename T>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *bucket_ptrs,

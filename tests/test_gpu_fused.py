@@ -98,6 +98,7 @@ def test_fused_dense_in_place_misaligned(dtype):
     run_case(w, 16, 1.0, in_place=True)            # output is the local gradient itself
     run_case(w, 16, 0.37, misalign=True)           # element-aligned local tensors
     run_case(w, 256, 1.0)                          # large alignment gaps
+    run_case(w, 16384, 0.37)                       # every tensor starts on a tile boundary
 
 
 def test_fused_tiny_and_many_tensors():

@@ -418,6 +418,7 @@ def full_step_check(name, align=16, scale=1.0):
 def test_full_step_small_workloads(name):
     full_step_check(name)
     full_step_check(name, align=wl.WORKLOADS[name].elem_size, scale=0.37)
+    full_step_check(name, align=16384, scale=0.5)       # every tensor starts on a tile boundary
 
 
 def test_full_step_vit_b16():

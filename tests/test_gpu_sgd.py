@@ -76,6 +76,7 @@ def test_sgd_ragged(dtype):
     run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, misalign=True)           # 4-byte aligned parameters
     run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, bucket_shift=1)          # element-aligned buckets
     run_sgd(w, 16, 1.0, 0.1, 0.0, 0.0, steps=1)                  # plain SGD
+    run_sgd(w, 16384, 0.5, 0.1, 0.9, 5e-4)                       # every tensor starts on a tile boundary
 
 
 def test_sgd_tiny_and_many_tensors():

@@ -135,7 +135,7 @@ def check_tiles(plan, numels, es):
 @settings(max_examples=150, deadline=None)
 @given(numels=st.lists(st.one_of(st.integers(0, 40), st.integers(0, 30000)), min_size=0, max_size=30),
        dtype=st.sampled_from(["f32", "bf16"]), cap=st.sampled_from([0, 64, 4096, 65536, 200000]),
-       lg=st.integers(0, 7))
+       lg=st.integers(0, 12))
 def test_layout_and_tiles_vs_checker(numels, dtype, cap, lg):
     es = 4 if dtype == "f32" else 2
     align = es << lg
@@ -148,7 +148,7 @@ def test_layout_and_tiles_vs_checker(numels, dtype, cap, lg):
 def test_layout_workloads_vs_checker():
     for name in wl.WORKLOAD_ORDER:
         w = wl.WORKLOADS[name]
-        for align in (16, w.elem_size, 256):
+        for align in (16, w.elem_size, 256, 16384):
             plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, align)
             assert layout_of(plan) == oracle.assign_buckets(w.numels, w.elem_size, w.bucket_cap_bytes, align)
             plan.close()
@@ -164,7 +164,7 @@ def test_layout_workloads_vs_checker():
 
 def test_plan_argument_errors():
     for args in (([1, 2], "f32", -1, 16), ([1, -2], "f32", 0, 16), ([1], "f32", 0, 3), ([1], "f32", 0, 2),
-                 ([1], "f32", 0, 8192), ([1], "bf16", 0, 1), ([1], "f32", 0, 24)):
+                 ([1], "f32", 0, 32768), ([1], "bf16", 0, 1), ([1], "f32", 0, 24)):
         with pytest.raises(kt.KtError) as ei:
             kt.Plan(*args)
         assert ei.value.status_name == "KT_EINVAL"
