@@ -284,6 +284,73 @@ def cpu_baseline(st, budget_elems):
                                     % (single[-1], payload1, secs1)}
 
 
+def two_level(dev, name="vit_b16", reps=5):
+    """The two-level combination (reduction inside each group of homogeneous devices, then
+    across groups through host memory) on one workload: 8 peers in 2 groups of 4; level 1
+    reduces this device's group on the GPU, level 2 combines its result with the other
+    group's result, which it reads straight from pinned host memory (the stand-in for the
+    relay between groups).  Context: what the host hop costs next to the flat K = 8 reduce."""
+    import ctypes
+    import torch
+    import paper_2505_10183_amd as kt
+    from paper_2505_10183_amd import workloads as wl
+    w = wl.WORKLOADS[name]
+    K, G = w.K, 2
+    group_of = [0] * (K // 2) + [1] * (K - K // 2)
+    plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
+    shares, flat_w = kt.kt_plan_shares(w.throughputs, w.global_batch)
+    w1, w2, _ = kt.kt_plan_group_weights(shares, group_of, G)
+    nb, elems, td = plan.num_buckets, plan.bucket_elems(), wl.torch_dtype(w.dtype)
+    mine = [k for k in range(K) if group_of[k] == 0]
+    peers = [[wl.flat_normal(n, w.dtype, w.sigma, 31 * k + b, dev) for b, n in enumerate(elems)] for k in range(K)]
+    y0 = [torch.empty(n, dtype=td, device=dev) for n in elems]
+    remote = [torch.empty(n, dtype=td, pin_memory=True).normal_(0, w.sigma) for n in elems]
+    out = [torch.empty(n, dtype=td, device=dev) for n in elems]
+    a_l1 = plan.marshal([peers[k][b] for b in range(nb) for k in mine])
+    a_l2 = plan.marshal([t for b in range(nb) for t in (y0[b], remote[b])])
+    a_flat = plan.marshal([peers[k][b] for b in range(nb) for k in range(K)])
+    a_y0, a_out = plan.marshal(y0), plan.marshal(out)
+    c_w1 = (ctypes.c_float * len(mine))(*[w1[k] for k in mine])
+    c_w2 = (ctypes.c_float * G)(*w2)
+    c_wf = (ctypes.c_float * K)(*flat_w)
+
+    def loop(fn):
+        fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    ms1 = loop(lambda: plan.kt_weighted_reduce(-1, a_l1, len(mine), c_w1, a_y0))
+    ms2 = loop(lambda: plan.kt_weighted_reduce(-1, a_l2, G, c_w2, a_out))
+    msf = loop(lambda: plan.kt_weighted_reduce(-1, a_flat, K, c_wf, a_out))
+    byts = w.total_elems * w.elem_size
+    return {"workload": name, "groups": "2 groups of %d devices" % (K // 2),
+            "level1_ms": round(ms1, 4), "level1_GBps": round((len(mine) + 1) * byts / ms1 / 1e6, 1),
+            "level2_from_pinned_host_ms": round(ms2, 4),
+            "level2_host_read_GBps": round(byts / ms2 / 1e6, 1),
+            "flat_reduce_ms": round(msf, 4)}
+
+
+def host_rows():
+    """Wall time of the host-only entry points at a realistic size (milliseconds)."""
+    import paper_2505_10183_amd as kt
+    shares, _ = kt.kt_plan_shares([1, 1, .8, .8, .6, .6, .4, .4], 1024)
+    t0 = time.perf_counter()
+    idx = kt.kt_sampler_epoch(1281167, 1024, shares, 1, 0, 3)
+    t1 = time.perf_counter()
+    ema = [0.0] * 8
+    for _ in range(1000):
+        ema, shares, _ = kt.kt_replan_shares([1.0, 1.1, 1.3, 1.2, 1.7, 1.6, 2.4, 2.6], shares, ema, 0.2, 1024)
+    t2 = time.perf_counter()
+    return {"sampler_epoch_N1281167_B1024_K8_ms": round((t1 - t0) * 1e3, 2), "indices": len(idx),
+            "replan_shares_K8_us": round((t2 - t1) * 1e3, 3)}
+
+
 def load_probe():
     """bench_probe.hip built beside this file (libkt_bench_probe.so); None if it is not built."""
     import ctypes
@@ -540,6 +607,14 @@ def main():
             also[name] = {"error": repr(exc)}
         torch.cuda.empty_cache()
 
+    extra = {}
+    if not args.no_ceilings:
+        for key, fn in (("two_level", lambda: two_level(dev)), ("host_rows", host_rows)):
+            try:
+                extra[key] = fn()
+            except Exception as exc:             # noqa: BLE001
+                print("bench.py: %s skipped: %r" % (key, exc), file=sys.stderr)
+        torch.cuda.empty_cache()
     ceil = None
     if not args.no_ceilings:
         try:
@@ -581,6 +656,8 @@ def main():
                                        "command, not of this run; null once the kernel sources have changed)" % w.name},
         "memory_system": ceil,
         "cpu_baseline": cpu,
+        "two_level": extra.get("two_level"),
+        "host_rows": extra.get("host_rows"),
         "also": also,
     }
     print(json.dumps(line))

@@ -57,6 +57,9 @@
 extern "C" {
 #endif
 
+/* The entry points below are the only symbols the shared library exports. */
+#define KT_API __attribute__((visibility("default")))
+
 typedef struct kt_plan kt_plan;
 
 typedef enum { KT_F32 = 0, KT_BF16 = 1 } kt_dtype;
@@ -74,13 +77,13 @@ typedef enum {
 #define KT_ALL_BUCKETS (-1)
 
 /* Library version string, static storage. */
-const char *kt_version(void);
+KT_API const char *kt_version(void);
 
 /* Text for a status code, static storage. */
-const char *kt_status_string(kt_status s);
+KT_API const char *kt_status_string(kt_status s);
 
 /* Message of the last failing call on this thread, static storage ("" if none). */
-const char *kt_last_error(void);
+KT_API const char *kt_last_error(void);
 
 /*
  * Load-adaptive batch shares (Sec. III-C, phase 2: the display equation and
@@ -100,7 +103,7 @@ const char *kt_last_error(void);
  * Errors: KT_EINVAL for NULL thr/shares, K < 1, K > KT_MAX_PEERS, B out of
  * range, a throughput that is not finite and positive, weights with B == 0.
  */
-kt_status kt_plan_shares(const double *thr, int K, int64_t B,
+KT_API kt_status kt_plan_shares(const double *thr, int K, int64_t B,
                          int64_t *shares, float *weights);
 
 /*
@@ -117,7 +120,7 @@ kt_status kt_plan_shares(const double *thr, int K, int64_t B,
  * not finite and positive, a device without any estimate); on error nothing
  * is written.
  */
-kt_status kt_replan_shares(const double *step_time, const int64_t *shares_used,
+KT_API kt_status kt_replan_shares(const double *step_time, const int64_t *shares_used,
                            double *ema, double alpha, int K, int64_t B,
                            int64_t *shares, float *weights);
 
@@ -136,7 +139,7 @@ kt_status kt_replan_shares(const double *step_time, const int64_t *shares_used,
  *   group_batch[G] host, out: optional (may be NULL), the B_g.
  * Errors: KT_EINVAL (NULL, ranges, a group without samples).
  */
-kt_status kt_plan_group_weights(const int64_t *shares, int K,
+KT_API kt_status kt_plan_group_weights(const int64_t *shares, int K,
                                 const int *group_of, int G, float *w_intra,
                                 float *w_inter, int64_t *group_batch);
 
@@ -160,9 +163,9 @@ kt_status kt_plan_group_weights(const int64_t *shares, int K,
  *   count     host, out: entries written (may be NULL in kt_sampler_epoch).
  * Errors: KT_EINVAL (arguments, capacity too small), KT_ENOMEM.
  */
-kt_status kt_sampler_epoch_size(int64_t N, int64_t B, const int64_t *shares,
+KT_API kt_status kt_sampler_epoch_size(int64_t N, int64_t B, const int64_t *shares,
                                 int K, int rank, int drop_last, int64_t *count);
-kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
+KT_API kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
                            uint64_t seed, uint64_t epoch, int shuffle, int rank,
                            int drop_last, int64_t *out, int64_t capacity,
                            int64_t *count);
@@ -192,25 +195,25 @@ kt_status kt_sampler_epoch(int64_t N, int64_t B, const int64_t *shares, int K,
  * Errors: KT_EINVAL (arguments), KT_ENOMEM, KT_EUNSUPPORTED (the plan would
  * need 2^24 or more 16 KiB tiles, i.e. 256 GiB per peer).
  */
-kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt,
+KT_API kt_status kt_plan_create(const int64_t *numel, int T, kt_dtype dt,
                          int64_t cap_bytes, int align_bytes, kt_plan **out);
 
 /* Releases host tables and, if uploaded, the device tables (waits for the
  * device to go idle first).  NULL is accepted. */
-kt_status kt_plan_destroy(kt_plan *plan);
+KT_API kt_status kt_plan_destroy(kt_plan *plan);
 
 /* Number of buckets / tensors; -1 for a NULL plan. */
-int kt_plan_num_buckets(const kt_plan *plan);
-int kt_plan_num_tensors(const kt_plan *plan);
+KT_API int kt_plan_num_buckets(const kt_plan *plan);
+KT_API int kt_plan_num_tensors(const kt_plan *plan);
 
 /* Bucket b: length in elements (padding included; the caller allocates
  * n_elems * element size bytes per bucket buffer), first tensor, tensor
  * count.  Any out-pointer may be NULL. */
-kt_status kt_plan_bucket_info(const kt_plan *plan, int b, int64_t *n_elems,
+KT_API kt_status kt_plan_bucket_info(const kt_plan *plan, int b, int64_t *n_elems,
                               int *first_tensor, int *n_tensors);
 
 /* Tensor t: its bucket and element offset inside it.  Out-pointers may be NULL. */
-kt_status kt_plan_tensor_info(const kt_plan *plan, int t, int *bucket,
+KT_API kt_status kt_plan_tensor_info(const kt_plan *plan, int t, int *bucket,
                               int64_t *elem_offset);
 
 /*
@@ -222,8 +225,8 @@ kt_status kt_plan_tensor_info(const kt_plan *plan, int t, int *bucket,
  * elements of the tile; n_tensors == 0 marks a tile wholly inside tensor
  * first_tensor.  Out-pointers may be NULL.
  */
-int64_t kt_plan_num_tiles(const kt_plan *plan);
-kt_status kt_plan_tile_info(const kt_plan *plan, int64_t i, int *bucket,
+KT_API int64_t kt_plan_num_tiles(const kt_plan *plan);
+KT_API kt_status kt_plan_tile_info(const kt_plan *plan, int64_t i, int *bucket,
                             int64_t *tile_in_bucket, int *first_tensor,
                             int *n_tensors);
 
@@ -241,7 +244,7 @@ kt_status kt_plan_tile_info(const kt_plan *plan, int64_t i, int *bucket,
  * aligned pointers take the vector path, others a slower correct one.
  * Tensors and buckets must not overlap.
  */
-kt_status kt_bucket_pack(kt_plan *plan, int bucket,
+KT_API kt_status kt_bucket_pack(kt_plan *plan, int bucket,
                          const void *const *tensor_ptrs,
                          void *const *bucket_bufs, void *stream);
 
@@ -261,7 +264,7 @@ kt_status kt_bucket_pack(kt_plan *plan, int bucket,
  *                        error where detected (equal ranges are; partial
  *                        overlaps are undefined).
  */
-kt_status kt_weighted_reduce(kt_plan *plan, int bucket,
+KT_API kt_status kt_weighted_reduce(kt_plan *plan, int bucket,
                              const void *const *peer_bufs, int K,
                              const float *weights, void *const *out_bufs,
                              void *stream);
@@ -272,7 +275,7 @@ kt_status kt_weighted_reduce(kt_plan *plan, int bucket,
  * (bf16: widen, multiply, round to nearest-even).  Padding is not read into
  * any tensor and nothing outside the tensors is written.
  */
-kt_status kt_bucket_unpack_scale(kt_plan *plan, int bucket,
+KT_API kt_status kt_bucket_unpack_scale(kt_plan *plan, int bucket,
                                  const void *const *bucket_bufs, float scale,
                                  void *const *tensor_ptrs, void *stream);
 
@@ -298,7 +301,7 @@ kt_status kt_bucket_unpack_scale(kt_plan *plan, int bucket,
  *                               inputs is rejected where detected.
  * Padding positions of the peer buckets are not read into any output.
  */
-kt_status kt_fused_step(kt_plan *plan, int bucket,
+KT_API kt_status kt_fused_step(kt_plan *plan, int bucket,
                         const void *const *local_tensor_ptrs,
                         const void *const *peer_bufs, int K,
                         const float *weights, float scale,
@@ -322,7 +325,7 @@ kt_status kt_fused_step(kt_plan *plan, int bucket,
  *                                       16-byte alignment gives the vector path.
  * Parameters, momentum and buckets must not overlap.
  */
-kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
+KT_API kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
                                const void *const *bucket_bufs, float scale,
                                void *const *param_ptrs,
                                void *const *momentum_ptrs, float lr,
@@ -353,7 +356,7 @@ kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
  * different plans or pointers race on the array: serialise them.  Nothing in
  * the array needs to start at zero.
  */
-kt_status kt_fused_step_noalloc(kt_plan *plan, int bucket,
+KT_API kt_status kt_fused_step_noalloc(kt_plan *plan, int bucket,
                                 const void *const *local_tensor_ptrs,
                                 const void *const *peer_bufs, int K,
                                 const float *weights, float scale,

@@ -83,9 +83,13 @@ def test_noalloc_matches_fused_step_on_two_calls_in_a_row(dtype):
     warm = Case(wl.ragged_workload(dtype=dtype, K=2, seed=63, n_tensors=24), 1.0)
     warm.call()
     warm.check("warm-up")
+    # whatever the runtime itself sets up lazily for a stream (queues, kernel-argument pools)
+    # exists before memory is measured: the same kernels have run on the side stream once
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        torch.zeros(8, device=DEV).add_(1)          # the stream exists on the device before memory is measured
+        warm.call(stream=side)
+    side.synchronize()
+    warm.check("warm-up on the side stream")
     torch.cuda.synchronize()
     free_before = torch.cuda.mem_get_info()[0]
 
