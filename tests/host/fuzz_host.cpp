@@ -16,7 +16,7 @@ int main(int argc, char **argv) {
     int T = rng()%40; std::vector<int64_t> n(T);
     for (auto &x: n) { int m=rng()%4; x = m==0? rng()%8 : m==1? rng()%3000 : m==2? rng()%40000 : (rng()%5==0? 0 : rng()%200); }
     kt_dtype dt = (rng()&1)? KT_F32: KT_BF16; int es = dt==KT_F32?4:2;
-    int align = es << (rng()%8); if (align>4096) align=4096;
+    int align = es << (rng()%14); if (align>16384) align=16384;
     int64_t caps[]={0,64,1000,4096,65536,200000}; int64_t cap=caps[rng()%6];
     KtHostPlan hp; const char* msg="";
     kt_status st = kt_build_host_plan(n.data(), T, dt, cap, align, hp, &msg);

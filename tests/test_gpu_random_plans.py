@@ -32,7 +32,7 @@ def random_case(seed):
                            3: rng.integers(4000, 4200), 4: rng.integers(6000, 40000)}[int(k)]))
     dtype = "f32" if rng.integers(0, 2) else "bf16"
     es = 4 if dtype == "f32" else 2
-    align = int(rng.choice([es, 16, 16, 64, 1024]))
+    align = int(rng.choice([es, 16, 16, 64, 1024, 16384]))
     cap = int(rng.choice([0, 32 * 1024, 200 * 1024]))
     K = int(rng.integers(1, 10))
     thr = tuple(float(x) for x in np.round(rng.uniform(0.2, 1.0, size=K), 2))
@@ -41,7 +41,7 @@ def random_case(seed):
     return wl.Workload("rand%d" % seed, dtype, tuple((n,) for n in numels), thr, B, cap, 1e-3, 4000 + seed), align, scale
 
 
-@pytest.mark.parametrize("seed", range(16))
+@pytest.mark.parametrize("seed", range(24))
 def test_random_plan(seed):
     w, align, scale = random_case(seed)
     K, dtype = w.K, w.dtype

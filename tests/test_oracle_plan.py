@@ -204,7 +204,7 @@ def check_layout(numels, es, cap, align, L):
 @settings(max_examples=200, deadline=None)
 @given(numels=st.lists(st.integers(0, 3000), min_size=0, max_size=40),
        es=st.sampled_from([2, 4]), cap=st.sampled_from([0, 64, 1000, 4096, 20000]),
-       lg=st.integers(0, 6))
+       lg=st.integers(0, 12))
 def test_bucket_layout_invariants(numels, es, cap, lg):
     align = es << lg
     L = oracle.assign_buckets(numels, es, cap, align)
@@ -236,3 +236,11 @@ def test_bucket_layout_hand_example():
     assert L["tensor_bucket"] == [0, 0, 1, 1, 2, 3]
     assert L["tensor_offset"] == [0, 5, 0, 9, 0, 0]
     assert L["bucket_elems"] == [8, 10, 20, 2]
+    # alignment to 16384 bytes (the largest allowed): 4096 fp32 / 8192 bf16 elements
+    L = oracle.assign_buckets([5, 4096, 3, 4097], 4, 0, 16384)
+    assert L["tensor_offset"] == [0, 4096, 8192, 12288] and L["bucket_elems"] == [20480]
+    L = oracle.assign_buckets([5, 9000, 3], 2, 40000, 16384)
+    assert L["tensor_bucket"] == [0, 1, 2] and L["tensor_offset"] == [0, 0, 0]
+    assert L["bucket_elems"] == [8192, 16384, 8192]
+    with pytest.raises(ValueError):
+        oracle.assign_buckets([5], 4, 0, 32768)
