@@ -161,7 +161,12 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
     moms = [_t.zeros(t.numel(), dtype=_t.float32, device=dev) for t in st["local"]]
     a_p, a_v = p.marshal(params), p.marshal(moms)
     ms_sgd = loop(lambda: p.kt_bucket_unpack_sgd(-1, st["a_outs"], 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False))
-    del params, moms
+    # the same with a bf16 model copy written beside the binary32 master parameters (mixed precision)
+    models = [_t.zeros(t.numel(), dtype=_t.bfloat16, device=dev) for t in st["local"]]
+    a_m = p.marshal(models)
+    ms_sgd_master = loop(lambda: p.kt_bucket_unpack_sgd_master(-1, st["a_outs"], 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4,
+                                                               False))
+    del params, moms, models
     # the chained step recorded once into a HIP graph and replayed (launch-bound small sets);
     # optional context: a failure here must not take the headline measurement down
     ms_graph = None
@@ -198,6 +203,7 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
         "fused_buckets_per_s": st["nb"] / (ms_fused * 1e-3),
         "fused_inplace_ms": ms_fused_inplace, "fused_inplace_GBps": (K + 1) * s * e / (ms_fused_inplace * 1e-3) / 1e9,
         "unpack_sgd_ms": ms_sgd, "unpack_sgd_GBps": (s + 16) * e / (ms_sgd * 1e-3) / 1e9,
+        "unpack_sgd_master_ms": ms_sgd_master, "unpack_sgd_master_GBps": (s + 18) * e / (ms_sgd_master * 1e-3) / 1e9,
     }
     if ms_graph:
         res.update({"graph_step_ms": ms_graph, "graph_step_GBps": (K + 5) * s * e / (ms_graph * 1e-3) / 1e9,
@@ -451,8 +457,10 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
         view_v.append(flat_v[b][off:off + n])
     params = [torch.zeros(n, dtype=torch.float32, device=dev) for n in w.numels]
     moms = [torch.zeros(n, dtype=torch.float32, device=dev) for n in w.numels]
+    models = [torch.zeros(n, dtype=torch.bfloat16, device=dev) for n in w.numels]
     m = st["plan"].marshal
     a_vl, a_vo, a_vp, a_vv, a_p, a_v = m(view_l), m(view_o), m(view_p), m(view_v), m(params), m(moms)
+    a_m = m(models)
     a_l, a_s0, a_pe, a_ot, a_o, a_r, a_w = (st["a_local"], st["a_slot0"], st["a_peers"], st["a_others"], st["a_outs"],
                                             st["a_result"], st["a_w"])
 
@@ -481,6 +489,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
             "fused_views": (lambda: p.kt_fused_step(-1, a_vl, a_ot, K, a_w, 1.0, a_vo), (K + 1) * s),
             "fused_views_inplace": (lambda: p.kt_fused_step(-1, a_vl, a_ot, K, a_w, 1.0, a_vl), (K + 1) * s),
             "sgd": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False), s + 16),
+            "sgd_master": (lambda: p.kt_bucket_unpack_sgd_master(-1, a_o, 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4, False), s + 18),
             "sgd_views": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_vp, a_vv, 0.1, 0.9, 5e-4, False), s + 16),
         }
 

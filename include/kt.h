@@ -333,6 +333,30 @@ KT_API kt_status kt_bucket_unpack_sgd(kt_plan *plan, int bucket,
                                int first_step, void *stream);
 
 /*
+ * kt_bucket_unpack_sgd for mixed-precision training (the bf16 workload): the
+ * parameters updated in binary32 are the master copy; every updated value is
+ * also written, rounded to nearest-even, to a bf16 model-parameter tensor, the
+ * copy that the next forward and backward pass read.  Same arithmetic as
+ * kt_bucket_unpack_sgd for p' and v' (Sec. IV-B's optimizer), plus
+ *     model_t[i] = bf16(p')
+ * Buckets may be of either element type; 2 more bytes per element are written.
+ *
+ *   master_ptrs, momentum_ptrs host, in: T device pointers each, binary32.
+ *   model_ptrs                 host, in: T device pointers, bf16, numel[t]
+ *                                        elements, 2-byte aligned (8-byte
+ *                                        alignment gives the vector path);
+ *                                        written only.
+ * Master parameters, momentum, model parameters and buckets must not overlap.
+ */
+KT_API kt_status kt_bucket_unpack_sgd_master(kt_plan *plan, int bucket,
+                                             const void *const *bucket_bufs,
+                                             float scale, void *const *master_ptrs,
+                                             void *const *momentum_ptrs,
+                                             void *const *model_ptrs, float lr,
+                                             float momentum, float weight_decay,
+                                             int first_step, void *stream);
+
+/*
  * kt_fused_step for callers that cannot allocate device memory: code that runs
  * under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, same kernels and bit-identical results, but the

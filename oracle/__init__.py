@@ -25,7 +25,8 @@ What it computes (KAITIAN, Sec. III and III-C):
 * ``group_weights``, ``two_level_reduce`` -- reduction inside groups, then
                           across groups (Sec. III-A);
 * ``unpack_sgd``       -- unpack fused with SGD momentum / weight decay (the
-                          optimizer of Sec. IV-B);
+                          optimizer of Sec. IV-B); ``unpack_sgd_master`` adds
+                          the bf16 model copy of mixed-precision training;
 * ``replan_shares``    -- online adaptation of the shares from measured step
                           times (Sec. III-C phase 1).
 
@@ -85,6 +86,8 @@ def _c():
             fn = getattr(lib, name)
             fn.argtypes = [vp, i64, f32, vp, vp, f32, f32, f32, ctypes.c_int]
             fn.restype = None
+        lib.kto_f32_to_bf16.argtypes = [vp, i64, vp]
+        lib.kto_f32_to_bf16.restype = None
         lib.kto_bf16_widen.argtypes = [ctypes.c_uint16]
         lib.kto_bf16_widen.restype = ctypes.c_float
         lib.kto_bf16_round.argtypes = [ctypes.c_double]
@@ -426,6 +429,23 @@ def unpack_sgd(layout, buckets: Sequence[np.ndarray], numels: Sequence[int], sca
         new_p.append(p)
         new_v.append(v)
     return new_p, new_v
+
+
+def unpack_sgd_master(layout, buckets: Sequence[np.ndarray], numels: Sequence[int], scale: float,
+                      masters: Sequence[np.ndarray], momenta: Sequence[np.ndarray], lr: float, momentum: float,
+                      weight_decay: float, first_step: bool, dtype: str, mode: str = "D"):
+    """unpack_sgd for mixed-precision training: the binary32 parameters are the
+    master copy and the model that forward / backward use holds each updated
+    value rounded once, to nearest-even, to bf16.  Returns (masters, momenta,
+    models); models are uint16 bit patterns."""
+    new_p, new_v = unpack_sgd(layout, buckets, numels, scale, masters, momenta, lr, momentum, weight_decay,
+                              first_step, dtype, mode)
+    models = []
+    for p in new_p:
+        m = np.empty(p.size, dtype=np.uint16)
+        _c().kto_f32_to_bf16(p.ctypes.data, p.size, m.ctypes.data)
+        models.append(m)
+    return new_p, new_v, models
 
 
 # --------------------------------------------------------------------------

@@ -189,3 +189,11 @@ void kto_sgd_bf16_S(const uint16_t *x, int64_t n, float scale, float *p, float *
         v[i] = vn;
     }
 }
+
+/* ---- mixed precision: the bf16 model copy of binary32 master parameters ----
+ * model[i] = p[i] rounded to nearest-even to bf16 (one rounding; NaN quiet). */
+void kto_f32_to_bf16(const float *p, int64_t n, uint16_t *model)
+{
+    for (int64_t i = 0; i < n; ++i) model[i] = kto_bf16_round((double)p[i]);
+}
+

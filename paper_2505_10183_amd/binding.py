@@ -72,6 +72,9 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp), c.c_float,
                                            c.c_float, c.c_float, i32, vp]
         L.kt_bucket_unpack_sgd.restype = i32
+        L.kt_bucket_unpack_sgd_master.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp),
+                                                  c.POINTER(vp), c.c_float, c.c_float, c.c_float, i32, vp]
+        L.kt_bucket_unpack_sgd_master.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -297,3 +300,14 @@ class Plan:
                                           self._arr(momenta, T, "tensor_ptrs (momentum)"), float(lr),
                                           float(momentum), float(weight_decay), int(bool(first_step)),
                                           _stream(stream)))
+
+    def kt_bucket_unpack_sgd_master(self, bucket: int, bucket_bufs, scale: float, masters, momenta, models,
+                                    lr: float, momentum: float, weight_decay: float, first_step: bool, stream=None):
+        """Mixed precision: binary32 master parameters and momentum updated in place, bf16 model copy written."""
+        T, nb = len(self.numels), self.num_buckets
+        _check(lib().kt_bucket_unpack_sgd_master(self._h, bucket, self._arr(bucket_bufs, nb, "bucket_bufs"),
+                                                 float(scale), self._arr(masters, T, "tensor_ptrs (master parameters)"),
+                                                 self._arr(momenta, T, "tensor_ptrs (momentum)"),
+                                                 self._arr(models, T, "tensor_ptrs (model parameters)"), float(lr),
+                                                 float(momentum), float(weight_decay), int(bool(first_step)),
+                                                 _stream(stream)))

@@ -627,12 +627,13 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
     KT_GUARD_END("kt_fused_step")
 }
 
-extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
-                                          void *const *param_ptrs, void *const *momentum_ptrs, float lr,
-                                          float momentum, float weight_decay, int first_step, void *stream)
+// kt_bucket_unpack_sgd and its mixed-precision form (model_ptrs != NULL).
+static kt_status unpack_sgd_impl(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
+                                 void *const *param_ptrs, void *const *momentum_ptrs, void *const *model_ptrs,
+                                 bool master, float lr, float momentum, float weight_decay, int first_step,
+                                 void *stream, const char *who)
 {
     KT_GUARD_BEGIN
-    const char *who = "kt_bucket_unpack_sgd";
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     std::lock_guard<std::mutex> lock(p->mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -640,7 +641,7 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     int64_t tile0, ntiles;
     kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
     if (st != KT_OK || ntiles == 0) return st;
-    if (!bucket_bufs || !param_ptrs || !momentum_ptrs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    if (!bucket_bufs || !param_ptrs || !momentum_ptrs || (master && !model_ptrs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
     if (first_step && capturing(s)) {
         kt_set_error("%s: first_step is frozen into a recorded kernel and would reset the momentum on every replay; "
                      "make the first step outside stream capture", who);
@@ -648,16 +649,18 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     }
     const KtHostPlan &hp = p->hp;
     const size_t T = hp.t_numel.size(), nb = hp.b_elems.size();
-    // table layout: [parameters T | momentum T | buckets nb]
-    std::vector<uint64_t> &vals = call_table(2 * T + nb);
+    const size_t M = master ? T : 0;
+    // table layout: [parameters T | momentum T | model parameters T (mixed precision only) | buckets nb]
+    std::vector<uint64_t> &vals = call_table(2 * T + M + nb);
     for (size_t t = 0; t < T; ++t) {
         vals[t] = reinterpret_cast<uintptr_t>(param_ptrs[t]);
         vals[T + t] = reinterpret_cast<uintptr_t>(momentum_ptrs[t]);
+        if (master) vals[2 * T + t] = reinterpret_cast<uintptr_t>(model_ptrs[t]);
     }
-    for (size_t b = 0; b < nb; ++b) vals[2 * T + b] = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
+    for (size_t b = 0; b < nb; ++b) vals[2 * T + M + b] = reinterpret_cast<uintptr_t>(bucket_bufs[b]);
     bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
     for (int b = b0; b < b1; ++b) {
-        const uintptr_t bp = vals[2 * T + b], bn = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+        const uintptr_t bp = vals[2 * T + M + b], bn = (uintptr_t)hp.b_elems[b] * hp.elem_size;
         if (bn && !bp) { kt_set_error("%s: NULL buffer for bucket %d", who, b); return KT_EINVAL; }
         if (bp & ((uintptr_t)hp.elem_size - 1)) { kt_set_error("%s: bucket %d buffer not aligned to the element size", who, b); return KT_EALIGN; }
         if (bp & (KT_VEC_BYTES - 1)) vec = false;
@@ -669,6 +672,15 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
                 kt_set_error("%s: parameters, momentum and bucket of tensor %d overlap", who, t);
                 return KT_EINVAL;
             }
+            if (master) {
+                const uintptr_t mp = vals[2 * T + t], mn = (uintptr_t)hp.t_numel[t] * 2;
+                if (mn && !mp) { kt_set_error("%s: NULL model-parameter pointer for tensor %d", who, t); return KT_EINVAL; }
+                if (mp & 1u) { kt_set_error("%s: tensor %d model parameters not 2-byte aligned", who, t); return KT_EALIGN; }
+                if (mn && ((mp < pp + tn && pp < mp + mn) || (mp < vp + tn && vp < mp + mn) || (mp < bp + bn && bp < mp + mn))) {
+                    kt_set_error("%s: model parameters of tensor %d overlap its parameters, momentum or bucket", who, t);
+                    return KT_EINVAL;
+                }
+            }
         }
     }
     st = ensure_device(p, s);
@@ -678,10 +690,27 @@ extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *co
     if (st != KT_OK) return st;
     uint64_t *d = static_cast<uint64_t *>(slot->dev);
     KtSgd a{scale, lr, momentum, weight_decay, first_step ? 1 : 0};
-    int e = kt_launch_unpack_sgd(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d + 2 * T),
-                                 reinterpret_cast<void *const *>(d), reinterpret_cast<void *const *>(d + T), a, vec,
-                                 stream);
-    if (e != 0) return hip_fail("kt_bucket_unpack_sgd: launch", (hipError_t)e);
+    int e = kt_launch_unpack_sgd(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d + 2 * T + M),
+                                 reinterpret_cast<void *const *>(d), reinterpret_cast<void *const *>(d + T),
+                                 master ? reinterpret_cast<void *const *>(d + 2 * T) : nullptr, a, vec, stream);
+    if (e != 0) { kt_set_error("%s: launch: %s", who, hipGetErrorString((hipError_t)e)); return KT_EHIP; }
     return mark_used(p, slot, s);
-    KT_GUARD_END("kt_bucket_unpack_sgd")
+    KT_GUARD_END(who)
+}
+
+extern "C" kt_status kt_bucket_unpack_sgd(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
+                                          void *const *param_ptrs, void *const *momentum_ptrs, float lr,
+                                          float momentum, float weight_decay, int first_step, void *stream)
+{
+    return unpack_sgd_impl(p, bucket, bucket_bufs, scale, param_ptrs, momentum_ptrs, nullptr, false, lr, momentum,
+                           weight_decay, first_step, stream, "kt_bucket_unpack_sgd");
+}
+
+extern "C" kt_status kt_bucket_unpack_sgd_master(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
+                                                 void *const *master_ptrs, void *const *momentum_ptrs,
+                                                 void *const *model_ptrs, float lr, float momentum,
+                                                 float weight_decay, int first_step, void *stream)
+{
+    return unpack_sgd_impl(p, bucket, bucket_bufs, scale, master_ptrs, momentum_ptrs, model_ptrs, true, lr, momentum,
+                           weight_decay, first_step, stream, "kt_bucket_unpack_sgd_master");
 }

@@ -89,6 +89,7 @@ struct KtSgd {
 int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                          int64_t ntiles, const void *const *d_bucket_ptrs,
                          void *const *d_param_ptrs, void *const *d_mom_ptrs,
+                         void *const *d_model_ptrs /* NULL: no bf16 model copy */,
                          const KtSgd &a, bool vector_ok, void *stream);
 
 // ---- shared between the C ABI (kt_api.cpp) and the entry point that

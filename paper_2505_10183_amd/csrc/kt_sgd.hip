@@ -59,6 +59,16 @@ __device__ __forceinline__ void sgd_quad(const Quad<uint16_t> &g, u32x4 &p, u32x
     }
 }
 
+// Mixed precision: the four updated binary32 master values of a quad are also
+// written, rounded to nearest-even, as four bf16 model parameters (8 bytes).
+__device__ __forceinline__ void st_model_quad(void *m, u32x4 p)
+{
+    u32x2 o;
+    o[0] = f32_to_bf16(__uint_as_float(p[0])) | (f32_to_bf16(__uint_as_float(p[1])) << 16);
+    o[1] = f32_to_bf16(__uint_as_float(p[2])) | (f32_to_bf16(__uint_as_float(p[3])) << 16);
+    __builtin_nontemporal_store(o, (KT_GLOBAL u32x2 *)m);
+}
+
 // one 16-byte gradient vector against its 4 (fp32) or 8 (bf16) parameters
 template <typename T> struct SgdVec;
 template <> struct SgdVec<float> {
@@ -91,10 +101,12 @@ template <> struct SgdVec<uint16_t> {
     }
 };
 
-// Mixed tile: tv.ptr = parameters, tv.ptr2 = momentum of the owning tensor.
-template <typename T, typename V>
+// Mixed tile: tv.ptr = parameters, tv.ptr2 = momentum of the owning tensor;
+// model (MASTER only) = the bf16 model-parameter pointers of the tile's tensors,
+// read from the global pointer table (mixed tiles are the rare ones).
+template <typename T, bool MASTER, typename V>
 __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n, const T *src,
-                                          const KtSgd &a, int vec_ok, int part, int parts)
+                                          const KtSgd &a, int vec_ok, int part, int parts, void *const *model)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int PV = SgdVec<T>::PV;
@@ -107,7 +119,8 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
             const int64_t r = e0 - tv.off[i];
             if (r + VE <= tv.numel[i]) {
                 const uintptr_t pa = tv.ptr[i] + (uintptr_t)r * 4, va = tv.ptr2[i] + (uintptr_t)r * 4;
-                if (((pa | va) & 15u) == 0) {
+                const uintptr_t ma = MASTER ? reinterpret_cast<uintptr_t>(model[i]) + (uintptr_t)r * 2 : 0;
+                if (((pa | va) & 15u) == 0 && (ma & 7u) == 0) {
                     u32x4 pr[PV], vr[PV];
                     const u32x4 gr = ld_vec(src + e0);
 #pragma unroll
@@ -121,6 +134,7 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
                     for (int h = 0; h < PV; ++h) {
                         st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
                         st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
+                        if (MASTER) st_model_quad(reinterpret_cast<void *>(ma + 8 * h), pr[h]);
                     }
                     continue;
                 }
@@ -139,6 +153,7 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
                 sgd_elem(widen(ld_elem(src + e)), pv, vv, a);
                 st_elem(pe, pv);
                 st_elem(ve, vv);
+                if (MASTER) st_elem(reinterpret_cast<uint16_t *>(model[i]) + r, (uint16_t)f32_to_bf16(pv));
             }
         }
     }
@@ -161,8 +176,9 @@ template <typename T> struct SgdShape {
 
 // A full solid tile's share of one workgroup: QB quads per lane, every load
 // issued before the first store.
-template <typename T>
-__device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x4 *v4, int part, const KtSgd &a)
+template <typename T, bool MASTER>
+__device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x4 *v4, u32x2 *m2, int part,
+                                              const KtSgd &a)
 {
     constexpr int QB = SgdShape<T>::QB;
     const int tid = threadIdx.x;
@@ -184,14 +200,15 @@ __device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x
         sgd_quad(gr[u], pr[u], vr[u], a);
         st_vec(p4 + idx, pr[u]);
         st_vec(v4 + idx, vr[u]);
+        if (MASTER) st_model_quad(m2 + idx, pr[u]);
     }
 }
 
-template <typename T>
+template <typename T, bool MASTER>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *bucket_ptrs,
                                                                  void *const *param_ptrs, void *const *mom_ptrs,
-                                                                 KtSgd a, int vec_ok)
+                                                                 void *const *model_ptrs, KtSgd a, int vec_ok)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
@@ -211,13 +228,16 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
         const int64_t rel = g.start - tb.t_off[tl.t0];
         float *pp = reinterpret_cast<float *>(param_ptrs[tl.t0]) + rel;
         float *vp = reinterpret_cast<float *>(mom_ptrs[tl.t0]) + rel;
-        if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0) {
+        uint16_t *mp = MASTER ? reinterpret_cast<uint16_t *>(model_ptrs[tl.t0]) + rel : nullptr;
+        if (((reinterpret_cast<uintptr_t>(pp) | reinterpret_cast<uintptr_t>(vp)) & 15u) == 0 &&
+            (reinterpret_cast<uintptr_t>(mp) & 7u) == 0) {
             const Quad<T> *s4 = reinterpret_cast<const Quad<T> *>(src + g.start);
             u32x4 *p4 = reinterpret_cast<u32x4 *>(pp);
             u32x4 *v4 = reinterpret_cast<u32x4 *>(vp);
+            u32x2 *m2 = reinterpret_cast<u32x2 *>(mp);
             const int nq = (int)((g.end - g.start) / 4);
             if (nq == QPT * KT_BLOCK) {
-                sgd_full_tile<T>(src + g.start, p4, v4, part, a);
+                sgd_full_tile<T, MASTER>(src + g.start, p4, v4, m2, part, a);
             } else {
 #pragma unroll 1
                 for (int idx = part * KT_BLOCK + tid; idx < nq; idx += SPLIT * KT_BLOCK) {
@@ -227,6 +247,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
                     sgd_quad(gq, pr, vr, a);
                     st_vec(p4 + idx, pr);
                     st_vec(v4 + idx, vr);
+                    if (MASTER) st_model_quad(m2 + idx, pr);
                 }
             }
             return;
@@ -239,10 +260,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
     const void *const *mp = reinterpret_cast<const void *const *>(mom_ptrs);
     if (nt <= KT_LDS_TENSORS) {
         const LdsView tv = stage_lds(lds, tb, pp, mp, tl.t0, nt);
-        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT);
+        sgd_mixed<T, MASTER>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT, MASTER ? model_ptrs + tl.t0 : nullptr);
     } else {
         const GlobalView tv = global_view(tb, pp, mp, tl.t0);
-        sgd_mixed<T>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT);
+        sgd_mixed<T, MASTER>(tv, nt, g, b_n, src, a, vec_ok, part, SPLIT, MASTER ? model_ptrs + tl.t0 : nullptr);
     }
 }
 
@@ -250,18 +271,22 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
 
 int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_t ntiles,
                          const void *const *d_bucket_ptrs, void *const *d_param_ptrs, void *const *d_mom_ptrs,
-                         const KtSgd &a, bool vector_ok, void *stream)
+                         void *const *d_model_ptrs, const KtSgd &a, bool vector_ok, void *stream)
 {
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     dim3 block(KT_BLOCK);
     // a grid may not hold 2^32 or more lanes
     const int split = dt == KT_F32 ? SgdShape<float>::SPLIT : SgdShape<uint16_t>::SPLIT;
     if (ntiles * split * KT_BLOCK >= ((int64_t)1 << 32)) return (int)hipErrorInvalidConfiguration;
-    if (dt == KT_F32)
-        kt_unpack_sgd_kernel<float><<<dim3((unsigned)(ntiles * SgdShape<float>::SPLIT)), block, 0, s>>>(
-            tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
-    else
-        kt_unpack_sgd_kernel<uint16_t><<<dim3((unsigned)(ntiles * SgdShape<uint16_t>::SPLIT)), block, 0, s>>>(
-            tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, a, vector_ok ? 1 : 0);
+    const dim3 grid((unsigned)(ntiles * split));
+    const int v = vector_ok ? 1 : 0;
+#define KT_SGD_LAUNCH(TT, MM) \
+    kt_unpack_sgd_kernel<TT, MM><<<grid, block, 0, s>>>(tb, tile0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, d_model_ptrs, a, v)
+    if (dt == KT_F32) {
+        if (d_model_ptrs) KT_SGD_LAUNCH(float, true); else KT_SGD_LAUNCH(float, false);
+    } else {
+        if (d_model_ptrs) KT_SGD_LAUNCH(uint16_t, true); else KT_SGD_LAUNCH(uint16_t, false);
+    }
+#undef KT_SGD_LAUNCH
     return (int)hipGetLastError();
 }

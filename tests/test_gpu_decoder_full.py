@@ -4,7 +4,8 @@ times: one batched launch per kernel over all 50 buckets, the reduce in place
 over peer slot 0.
 
 The GPU path runs once (module fixture): pack, reduce, unpack-scale; the fused
-single pass; two steps of unpack fused with SGD.  The checker then goes through
+single pass; two steps of unpack fused with SGD (the second through the
+mixed-precision entry, which also writes the bf16 model copy).  The checker then goes through
 the workload bucket by bucket.  Its inputs are the seeded tensors and peer
 buckets only: peer slot 0 is the checker's own pack of the local tensors, the
 reduced bucket is the checker's own reduce, and so on down the chain; nothing
@@ -133,11 +134,13 @@ def dec():
     moms = [torch.full((n,), float("nan"), device=DEV) for n in w.numels]     # not to be read on the first step
     plan.kt_bucket_unpack_sgd(-1, slot0, SGD_SCALES[0], params, moms, LR, MU, WD, True)
     p1, v1 = [t.clone() for t in params], [t.clone() for t in moms]
-    plan.kt_bucket_unpack_sgd(-1, slot0, SGD_SCALES[1], params, moms, LR, MU, WD, False)
+    # the second step through the mixed-precision entry: same update, plus the bf16 model copy
+    model = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in w.numels]
+    plan.kt_bucket_unpack_sgd_master(-1, slot0, SGD_SCALES[1], params, moms, model, LR, MU, WD, False)
     torch.cuda.synchronize()
     say("[decoder] device work done; %d host threads for the checker" % NTHREADS)
     yield dict(w=w, L=L, wts=wts, peers=peers, local=local, packed=packed, reduced=slot0, result=result, fused=fused,
-               p0=p0, p1=p1, v1=v1, p2=params, v2=moms, plan=plan)
+               p0=p0, p1=p1, v1=v1, p2=params, v2=moms, model=model, plan=plan)
     torch.cuda.empty_cache()
 
 
@@ -173,7 +176,8 @@ def test_decoder_every_element_of_every_bucket(dec, group):
         hp0 = [host(dec["p0"][t]) for t in ts]
         hv0 = [np.full(m, np.nan, np.float32) for m in numels]
         p1w, v1w = oracle.unpack_sgd(sub, [wantS], numels, SGD_SCALES[0], hp0, hv0, LR, MU, WD, True, "bf16", "S")
-        p2w, v2w = oracle.unpack_sgd(sub, [wantS], numels, SGD_SCALES[1], p1w, v1w, LR, MU, WD, False, "bf16", "S")
+        p2w, v2w, m2w = oracle.unpack_sgd_master(sub, [wantS], numels, SGD_SCALES[1], p1w, v1w, LR, MU, WD, False,
+                                                 "bf16", "S")
         for i, t in enumerate(ts):
             o, m = sub["tensor_offset"][i], numels[i]
             got_t = host(dec["result"][t])
@@ -185,7 +189,8 @@ def test_decoder_every_element_of_every_bucket(dec, group):
             for what, dev_t, want_t in (("parameters after step 1", dec["p1"][t], p1w[i]),
                                         ("momentum after step 1", dec["v1"][t], v1w[i]),
                                         ("parameters after step 2", dec["p2"][t], p2w[i]),
-                                        ("momentum after step 2", dec["v2"][t], v2w[i])):
+                                        ("momentum after step 2", dec["v2"][t], v2w[i]),
+                                        ("bf16 model copy after step 2", dec["model"][t], m2w[i])):
                 got_s = host(dev_t)
                 assert same_bits(got_s, want_t), "SGD %s, tensor %d: %s" % (what, t, first_diff(got_s, want_t))
         say("[decoder] bucket %d: %d tensors, %d elements, %d of them differ from the double-accumulated definition "

@@ -22,7 +22,7 @@ def announce(request):
     torch.cuda.synchronize()
 
 
-def run_sgd(w, align, scale, lr, mu, wd, steps=2, misalign=False, bucket_shift=0, per_bucket=False):
+def run_sgd(w, align, scale, lr, mu, wd, steps=2, misalign=False, bucket_shift=0, per_bucket=False, master=False):
     dtype = w.dtype
     plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, align)
     L = oracle.assign_buckets(w.numels, w.elem_size, w.bucket_cap_bytes, align)
@@ -34,6 +34,9 @@ def run_sgd(w, align, scale, lr, mu, wd, steps=2, misalign=False, bucket_shift=0
     v_store = [torch.full((n + 12,), 9.0, device=DEV) for n in w.numels]
     params = [s[l:l + n] for s, l, n in zip(p_store, lo, w.numels)]
     moms = [s[l:l + n] for s, l, n in zip(v_store, lo, w.numels)]
+    # mixed precision: the bf16 model copy, canary-guarded too (odd tensors only 2-byte aligned when misaligned)
+    m_store = [torch.full((n + 12,), 9.0, dtype=torch.bfloat16, device=DEV) for n in w.numels]
+    models = [s[l:l + n] for s, l, n in zip(m_store, lo, w.numels)]
     for p in params:
         p.copy_(torch.randn(p.shape, generator=gen, device=DEV))
     for v in moms:
@@ -44,14 +47,21 @@ def run_sgd(w, align, scale, lr, mu, wd, steps=2, misalign=False, bucket_shift=0
     for step in range(steps):
         store = [wl.flat_normal(n + 8, dtype, 1e-2, 900 + 10 * step + b, DEV) for b, n in enumerate(plan.bucket_elems())]
         bufs = [s[bucket_shift:bucket_shift + n] for s, n in zip(store, plan.bucket_elems())]
-        if per_bucket:
-            for b in range(nb):
+        for b in (range(nb) if per_bucket else [-1]):
+            if master:
+                plan.kt_bucket_unpack_sgd_master(b, bufs, scale, params, moms, models, lr, mu, wd, step == 0)
+            else:
                 plan.kt_bucket_unpack_sgd(b, bufs, scale, params, moms, lr, mu, wd, step == 0)
-        else:
-            plan.kt_bucket_unpack_sgd(-1, bufs, scale, params, moms, lr, mu, wd, step == 0)
         torch.cuda.synchronize()
         hb = [host(b) for b in bufs]
-        hp, hv = oracle.unpack_sgd(L, hb, w.numels, scale, hp, hv, lr, mu, wd, step == 0, dtype, "S")
+        if master:
+            hp, hv, hm = oracle.unpack_sgd_master(L, hb, w.numels, scale, hp, hv, lr, mu, wd, step == 0, dtype, "S")
+            for t, n in enumerate(w.numels):
+                assert host(models[t]).tobytes() == hm[t].tobytes(), ("model copy", step, t)
+                s_, l = m_store[t], lo[t]
+                assert bool((s_[:l] == 9.0).all()) and bool((s_[l + n:] == 9.0).all()), ("model canary", t)
+        else:
+            hp, hv = oracle.unpack_sgd(L, hb, w.numels, scale, hp, hv, lr, mu, wd, step == 0, dtype, "S")
         hpD, hvD = oracle.unpack_sgd(L, hb, w.numels, scale, hpD, hvD, lr, mu, wd, step == 0, dtype, "D")
         for t, n in enumerate(w.numels):
             gp, gv = host(params[t]), host(moms[t])
@@ -79,13 +89,27 @@ def test_sgd_ragged(dtype):
     run_sgd(w, 16384, 0.5, 0.1, 0.9, 5e-4)                       # every tensor starts on a tile boundary
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sgd_master_ragged(dtype):
+    """Mixed precision: binary32 master parameters updated, bf16 model copy written."""
+    w = wl.ragged_workload(dtype=dtype, seed=92)
+    run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, master=True)
+    run_sgd(w, 16, 0.37, 0.05, 0.9, 5e-4, per_bucket=True, master=True)
+    run_sgd(w, w.elem_size, 1.0, 0.1, 0.9, 5e-4, master=True)               # dense packing
+    run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, misalign=True, master=True)         # 4-byte / 2-byte aligned tensors
+    run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, bucket_shift=1, master=True)        # element-aligned buckets
+    run_sgd(w, 16384, 0.5, 0.1, 0.9, 5e-4, master=True)
+
+
 def test_sgd_tiny_and_many_tensors():
     numels = [1, 3, 5, 7, 2, 1, 1, 6, 4, 1] * 100 + [30000] + [4] * 1500
     for dtype in ("f32", "bf16"):
         w = wl.Workload("tm", dtype, tuple((n,) for n in numels), (1.0,), 1, 0, 1e-2, 17)
         run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4)
+        run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, master=True)
 
 
 @pytest.mark.parametrize("name", ["mobilenetv2", "resnet18"])
 def test_sgd_workloads(name):
     run_sgd(wl.WORKLOADS[name], 16, 1.0, 0.1, 0.9, 5e-4, steps=2)
+    run_sgd(wl.WORKLOADS[name], 16, 1.0, 0.1, 0.9, 5e-4, steps=2, master=True)

@@ -335,6 +335,24 @@ def test_replan_errors_leave_state_untouched():
     assert L.kt_replan_shares(t2, u, e, 0.5, 2, 8, b, None) == 0 and sum(b) == 8
 
 
+def test_unpack_sgd_master_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "bf16", 0, 16)
+    ok_p, ok_v, ok_m, ok_b = [16000, 32000], [48000, 64000], [80000, 96000], [4096]
+    cases = [
+        (lambda: p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, ok_p, ok_v, [0, 96000], 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),
+        (lambda: p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, ok_p, ok_v, [80001, 96000], 0.1, 0.9, 0.0, True, stream=0), "KT_EALIGN"),
+        (lambda: p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, ok_p, ok_v, [16010, 96000], 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),   # over the master copy
+        (lambda: p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, ok_p, ok_v, [4100, 96000], 0.1, 0.9, 0.0, True, stream=0), "KT_EINVAL"),    # over the bucket
+        (lambda: p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, [16002, 32000], ok_v, ok_m, 0.1, 0.9, 0.0, True, stream=0), "KT_EALIGN"),
+    ]
+    for fn, want in cases:
+        with pytest.raises(kt.KtError) as ei:
+            fn()
+        assert ei.value.status_name == want, str(ei.value)
+    with pytest.raises(ValueError):
+        p.kt_bucket_unpack_sgd_master(-1, ok_b, 1.0, ok_p, ok_v, ok_m[:1], 0.1, 0.9, 0.0, True, stream=0)
+
+
 def test_binding_rejects_arrays_of_the_wrong_length():
     """The library copies whole pointer arrays whatever bucket is selected; the
     binding, which knows T, the bucket count and K, refuses arrays of any other

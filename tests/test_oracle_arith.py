@@ -463,3 +463,40 @@ def test_sgd_special_cases_and_modes():
     pp, vv = oracle.unpack_sgd(lay2, [bucket], [5, 3], 1.0, [np.zeros(5, np.float32), np.zeros(3, np.float32)],
                                [np.zeros(5, np.float32), np.zeros(3, np.float32)], 1.0, 0.0, 0.0, True, "f32", "S")
     assert list(vv[0]) == [0, 1, 2, 3, 4] and list(vv[1]) == [8, 9, 10] and list(pp[1]) == [-8, -9, -10]
+
+
+def test_sgd_master_model_copy_is_the_library_bf16_rounding():
+    """Mixed precision: the bf16 model copy equals torch's float32 -> bfloat16
+    conversion (round to nearest-even) of the updated master parameters, which
+    themselves equal the plain update; ties, overflow to infinity, NaN, signed
+    zeros and subnormals included."""
+    rng = np.random.default_rng(24)
+    n = 200000
+    x = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    p0 = rng.standard_normal(n).astype(np.float32)
+    v0 = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    lay = _one_tensor_layout(n)
+    for mode in "DS":
+        p, v = oracle.unpack_sgd(lay, [x], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "f32", mode)
+        pm, vm, mm = oracle.unpack_sgd_master(lay, [x], [n], 0.37, [p0], [v0], 0.1, 0.9, 5e-4, False, "f32", mode)
+        assert (pm[0] == p[0]).all() and (vm[0] == v[0]).all()
+        want = torch.from_numpy(p[0]).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+        assert (mm[0] == want).all()
+    # chosen master values through the model-copy step alone
+    bits = np.array([0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF,      # ties to even (down, up), just above, just below
+                     0x7F7FFFFF, 0xFF7FFFFF,                              # largest finite -> +-infinity
+                     0x7F800000, 0xFF800000, 0x7FC00001, 0x7F800001,      # infinities, quiet and signalling NaN
+                     0x00000000, 0x80000000, 0x00000001, 0x00008000, 0x00018000, 0x007FFFFF],   # zeros, subnormals
+                    dtype=np.uint32)
+    p_special = bits.view(np.float32).copy()
+    m = len(bits)
+    out = np.empty(m, np.uint16)
+    oracle._c().kto_f32_to_bf16(p_special.ctypes.data, m, out.ctypes.data)
+    mm = [out]
+    expect = [0x3F80, 0x3F82, 0x3F81, 0x3F80, 0x7F80, 0xFF80, 0x7F80, 0xFF80, None, None,
+              0x0000, 0x8000, 0x0000, 0x0000, 0x0002, 0x0080]
+    for got, want, b in zip(mm[0], expect, bits):
+        if want is None:
+            assert (got & 0x7F80) == 0x7F80 and (got & 0x007F) != 0 and (got & 0x0040), hex(b)    # a quiet NaN
+        else:
+            assert got == want, (hex(b), hex(got), hex(want))

@@ -140,3 +140,20 @@ def test_layout_and_sampler_mistakes_are_caught(monkeypatch):
 
     monkeypatch.setattr(oracle, "sampler_epoch", strided)
     expect_pin_fails(sampler_pins.test_partition_equal_devices_is_plain_split)
+
+
+def test_master_model_copy_mistakes_are_caught(monkeypatch):
+    good = oracle.unpack_sgd_master
+
+    def truncates_instead_of_rounding(*a, **k):
+        p, v, m = good(*a, **k)
+        return p, v, [(x.view(np.uint32) >> np.uint32(16)).astype(np.uint16) for x in p]
+
+    def copies_the_old_parameters(layout, buckets, numels, scale, masters, *rest, **k):
+        p, v, _ = good(layout, buckets, numels, scale, masters, *rest, **k)
+        _, _, m = good(layout, buckets, numels, 0.0, masters, rest[0], 0.0, 0.0, 0.0, True, *rest[5:], **k)
+        return p, v, m
+
+    for mutant in (truncates_instead_of_rounding, copies_the_old_parameters):
+        monkeypatch.setattr(oracle, "unpack_sgd_master", mutant)
+        expect_pin_fails(arith.test_sgd_master_model_copy_is_the_library_bf16_rounding)
