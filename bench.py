@@ -562,7 +562,7 @@ def main():
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no collectives); use --gpus 1", file=sys.stderr)
+        print("bench.py: the library runs on one GPU only (no collectives between GPUs); use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     global ALIGN_BYTES
@@ -608,8 +608,10 @@ def main():
     torch.cuda.empty_cache()
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         try:
-            r, s2 = time_workload(name, args.steps, args.warmup, dev, not args.out_of_place, args.misalign,
-                                  events_in_timed_loop=wl_total(name) >= 50_000_000)
+            # the context workloads are short: at least 100 timed steps after 20 warm-up steps
+            r, s2 = time_workload(name, max(args.steps, 100), max(args.warmup, 20), dev, not args.out_of_place,
+                                  args.misalign, events_in_timed_loop=wl_total(name) >= 50_000_000)
+            r["steps"], r["warmup"] = max(args.steps, 100), max(args.warmup, 20)
             also[name] = {k: (round(v, 4) if isinstance(v, float) else v) for k, v in r.items()}
             del s2
         except Exception as exc:                 # noqa: BLE001
