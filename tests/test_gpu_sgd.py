@@ -109,7 +109,7 @@ def test_sgd_tiny_and_many_tensors():
         run_sgd(w, 16, 1.0, 0.1, 0.9, 5e-4, master=True)
 
 
-@pytest.mark.parametrize("name", ["mobilenetv2", "resnet18"])
+@pytest.mark.parametrize("name", ["mobilenetv2", "resnet18", "vit_b16"])
 def test_sgd_workloads(name):
     run_sgd(wl.WORKLOADS[name], 16, 1.0, 0.1, 0.9, 5e-4, steps=2)
     run_sgd(wl.WORKLOADS[name], 16, 1.0, 0.1, 0.9, 5e-4, steps=2, master=True)
