@@ -133,3 +133,27 @@ def test_noalloc_recorded_into_a_graph_after_an_eager_call():
     torch.cuda.synchronize()
     other.call()
     other.check("eager after the refused capture")
+
+
+def test_noalloc_at_the_size_of_the_1p3b_set():
+    """The largest workload's plan (160 640 tiles, 292 tensors, 50 buckets: 2.6 MB of
+    tables in the 4 MiB array) with K = 2, against kt_fused_step bit for bit (the
+    fused pass itself is checked against the CPU checker at this size elsewhere)."""
+    w = wl.WORKLOADS["decoder_1p3b"]
+    plan_ref = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+    plan_na = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, 16)
+    nb = plan_ref.num_buckets
+    assert plan_na.num_tiles == 160640 and nb == 50
+    local = wl.gradient_set(w, 0, DEV)
+    peer1 = [wl.flat_normal(n, w.dtype, w.sigma, 8100 + b, DEV) for b, n in enumerate(plan_ref.bucket_elems())]
+    out_ref = [torch.empty_like(t) for t in local]
+    out_na = [torch.zeros_like(t) for t in local]
+    wts = [0.625, 0.375]
+    plan_ref.kt_fused_step(-1, local, peer1, 2, wts, 0.5, out_ref)
+    plan_na.kt_fused_step_noalloc(-1, local, peer1, 2, wts, 0.5, out_na)
+    plan_na.kt_fused_step_noalloc(-1, local, peer1, 2, wts, 0.5, out_na)       # tables already in place
+    torch.cuda.synchronize()
+    for t in range(len(local)):
+        assert torch.equal(out_na[t].view(torch.int16), out_ref[t].view(torch.int16)), t
+    del local, peer1, out_ref, out_na
+    torch.cuda.empty_cache()
