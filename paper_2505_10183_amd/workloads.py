@@ -15,6 +15,7 @@ to a tiny MLP, ResNet-18 (CIFAR head), ViT-B/16 and a 1.3B-parameter decoder.
 from __future__ import annotations
 
 from dataclasses import dataclass, field
+from functools import cached_property
 from typing import List, Sequence, Tuple
 
 import numpy as np
@@ -38,11 +39,11 @@ class Workload:
     def K(self) -> int:
         return len(self.throughputs)
 
-    @property
+    @cached_property
     def numels(self) -> List[int]:
         return [int(np.prod(s, dtype=np.int64)) for s in self.shapes]
 
-    @property
+    @cached_property
     def total_elems(self) -> int:
         return int(sum(self.numels))
 
