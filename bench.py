@@ -342,6 +342,32 @@ def two_level(dev, name="vit_b16", reps=5):
             "flat_reduce_ms": round(msf, 4)}
 
 
+def call_cost(dev, n=5000):
+    """Host cost of one device call on a launch-bound set (the MLP set, K = 2): wall time per
+    call over n back-to-back kt_weighted_reduce calls, through the binding and straight
+    through ctypes, next to PyTorch's own smallest launch (an in-place add on 1024 floats)."""
+    import torch
+    from paper_2505_10183_amd import binding
+    st = setup("mlp", dev)
+    p, K, L = st["plan"], st["K"], binding.lib()
+    stream = binding._stream(None)
+    x = torch.zeros(1024, device=dev)
+
+    def per_call(fn):
+        for _ in range(200):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return round((time.perf_counter() - t0) / n * 1e6, 2)
+
+    return {"binding_us": per_call(lambda: p.kt_weighted_reduce(-1, st["a_peers"], K, st["a_w"], st["a_outs"])),
+            "c_abi_us": per_call(lambda: L.kt_weighted_reduce(p._h, -1, st["a_peers"], K, st["a_w"], st["a_outs"], stream)),
+            "torch_add_us": per_call(lambda: x.add_(1))}
+
+
 def host_rows():
     """Wall time of the host-only entry points at a realistic size (milliseconds)."""
     import paper_2505_10183_amd as kt
@@ -620,7 +646,8 @@ def main():
 
     extra = {}
     if not args.no_ceilings:
-        for key, fn in (("two_level", lambda: two_level(dev)), ("host_rows", host_rows)):
+        for key, fn in (("two_level", lambda: two_level(dev)), ("host_rows", host_rows),
+                        ("call_cost", lambda: call_cost(dev))):
             try:
                 extra[key] = fn()
             except Exception as exc:             # noqa: BLE001
@@ -669,6 +696,7 @@ def main():
         "cpu_baseline": cpu,
         "two_level": extra.get("two_level"),
         "host_rows": extra.get("host_rows"),
+        "call_cost": extra.get("call_cost"),
         "also": also,
     }
     print(json.dumps(line))
