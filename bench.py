@@ -441,6 +441,13 @@ def ceilings(dev, reps=10):
     res.update({"copy_GBps": round(2 * gib / t_copy / 1e9, 1),
                 "reduce_8_reads_1_write_GBps": round(9 * gib / t_mix / 1e9, 1),
                 "reduce_8_reads_1_write_in_place_GBps": round(9 * gib / t_mix_in / 1e9, 1)})
+    # more peers than the kernels are specialised for (K > 8: peers taken in chunks)
+    more = [torch.empty(n, dtype=torch.float32, device=dev).normal_() for _ in range(8)]
+    a16 = plan.marshal(bufs + more)
+    w16 = (ctypes.c_float * 16)(*([0.0625] * 16))
+    t16 = loop(lambda: plan.kt_weighted_reduce(-1, a16, 16, w16, a0))
+    res["reduce_16_reads_1_write_in_place_GBps"] = round(17 * gib / t16 / 1e9, 1)
+    del more
     assert float(sink.abs().sum()) == 0.0
     return res
 

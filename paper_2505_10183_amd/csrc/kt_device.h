@@ -225,6 +225,58 @@ template <> struct Acc<uint16_t> {
     }
 };
 
+// ---- K > 8 -------------------------------------------------------------------
+// The peers are taken in chunks of at most Chunk<T>::N, ascending, with the
+// accumulators of the tile's vectors kept in registers across chunks, so that a
+// lane still has (vectors per lane) x (chunk) loads in flight at a time and the
+// per-element order of operations is the one of the definition (product for
+// k = 0, then one fused multiply-add per peer in ascending k).  `ptr(k)` gives
+// peer k's data at the tile start.
+template <typename T> struct Chunk;
+template <> struct Chunk<float> { static constexpr int N = 8; };       // 148 VGPRs, 3 waves per SIMD
+template <> struct Chunk<uint16_t> { static constexpr int N = 6; };    // 8 accumulators per vector: 6 keeps 3 waves per SIMD
+
+template <typename T, int KC, typename P>
+__device__ __forceinline__ void sum_chunk(Acc<T> *acc, P ptr, const KtWeights &wts, int k0, int tid)
+{
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    u32x4 r[VPT][KC];
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+        const u32x4 *x = reinterpret_cast<const u32x4 *>(ptr(k0 + j));
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) r[u][j] = ld_vec(x + u * KT_BLOCK + tid);
+    }
+#pragma unroll
+    for (int j = 0; j < KC; ++j) {
+        const float w = wts.w[k0 + j];
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) {
+            if (j == 0 && k0 == 0) acc[u].first(r[u][j], w); else acc[u].add(r[u][j], w);
+        }
+    }
+}
+
+// acc[u] = sum over all K peers of vector u of a full tile.
+template <typename T, typename P>
+__device__ __forceinline__ void sum_in_chunks(Acc<T> *acc, P ptr, const KtWeights &wts, int K, int tid)
+{
+    constexpr int CH = Chunk<T>::N;
+    int k0 = 0;
+#pragma unroll 1
+    for (; k0 + CH <= K; k0 += CH) sum_chunk<T, CH>(acc, ptr, wts, k0, tid);
+    switch (K - k0) {      // the last, shorter chunk (uniform over the grid)
+    case 1: sum_chunk<T, 1>(acc, ptr, wts, k0, tid); break;
+    case 2: sum_chunk<T, 2>(acc, ptr, wts, k0, tid); break;
+    case 3: sum_chunk<T, 3>(acc, ptr, wts, k0, tid); break;
+    case 4: sum_chunk<T, 4>(acc, ptr, wts, k0, tid); break;
+    case 5: sum_chunk<T, 5>(acc, ptr, wts, k0, tid); break;
+    case 6: if (CH > 6) sum_chunk<T, 6>(acc, ptr, wts, k0, tid); break;
+    case 7: if (CH > 7) sum_chunk<T, 7>(acc, ptr, wts, k0, tid); break;
+    default: break;
+    }
+}
+
 __device__ __forceinline__ float widen(float x) { return x; }
 __device__ __forceinline__ float widen(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
 template <typename T> __device__ __forceinline__ T narrow(float a);

@@ -153,6 +153,92 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
     }
 }
 
+// K > 8, 16-byte vectors: full solid tiles take the peers in chunks with the
+// accumulators in registers (sum_in_chunks; peer 0 is the local tensor); every
+// other tile goes vector by vector with a loop over the peers.
+template <typename T, typename V>
+__device__ __forceinline__ void fused_mixed_manyk(const V &tv, int nt, const TileGeom &g, int64_t b_n,
+                                                  const void *const *pp, int K, const KtWeights &wts, float scale)
+{
+    constexpr int VE = Elem<T>::VE;
+    const int nvec = (int)((g.end - g.start + VE - 1) / VE);
+#pragma unroll 1
+    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+        const int64_t e0 = g.start + (int64_t)v * VE;
+        int i = find_owner_v(tv, nt, e0);
+        if (i >= 0 && e0 + VE <= b_n) {
+            const int64_t r = e0 - tv.off[i];
+            if (r + VE <= tv.numel[i]) {
+                const uintptr_t ps = tv.ptr[i] + (uintptr_t)r * sizeof(T);
+                const uintptr_t pd = tv.ptr2[i] + (uintptr_t)r * sizeof(T);
+                if (((ps | pd) & 15u) == 0) {
+                    Acc<T> acc;
+                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), wts.w[0]);
+#pragma unroll 4
+                    for (int k = 1; k < K; ++k)
+                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k - 1]) + g.start) + v), wts.w[k]);
+                    st_vec(reinterpret_cast<void *>(pd), scale_vec<T>(acc.finish(), scale));
+                    continue;
+                }
+            }
+        }
+#pragma unroll 1
+        for (int q = 0; q < VE; ++q) {
+            const int64_t e = e0 + q;
+            if (e >= b_n) break;
+            while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
+            if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
+                const int64_t r = e - tv.off[i];
+                float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
+                for (int k = 1; k < K; ++k) a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
+                st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
+            }
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                  const void *const *local_ptrs,
+                                                                  const void *const *peer_ptrs, int K,
+                                                                  KtWeights wts, float scale, void *const *out_ptrs)
+{
+    constexpr int VE = Elem<T>::VE;
+    constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    __shared__ LdsTable lds;
+
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
+    const int tid = threadIdx.x;
+    const void *const *pp = peer_ptrs + (int64_t)g.bucket * (K - 1);   // peers 1..K-1 of this bucket
+
+    if (tl.nt == 0 && g.end - g.start == TILE_ELEMS) {
+        const int64_t rel = g.start - tb.t_off[tl.t0];
+        const T *src = reinterpret_cast<const T *>(local_ptrs[tl.t0]) + rel;
+        T *dst = reinterpret_cast<T *>(out_ptrs[tl.t0]) + rel;
+        if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0) {
+            Acc<T> acc[VPT];
+            sum_in_chunks<T>(acc, [&](int k) { return k == 0 ? src : reinterpret_cast<const T *>(pp[k - 1]) + g.start; },
+                             wts, K, tid);
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+                st_vec(reinterpret_cast<u32x4 *>(dst) + u * KT_BLOCK + tid, scale_vec<T>(acc[u].finish(), scale));
+            return;
+        }
+    }
+    const int nt = tl.nt == 0 ? 1 : tl.nt;
+    const int64_t b_n = tb.b_elems[g.bucket];
+    const void *const *op = reinterpret_cast<const void *const *>(out_ptrs);
+    if (nt <= KT_LDS_TENSORS) {
+        const LdsView tv = stage_lds(lds, tb, local_ptrs, op, tl.t0, nt);
+        fused_mixed_manyk<T>(tv, nt, g, b_n, pp, K, wts, scale);
+    } else {
+        const GlobalView tv = global_view(tb, local_ptrs, op, tl.t0);
+        fused_mixed_manyk<T>(tv, nt, g, b_n, pp, K, wts, scale);
+    }
+}
+
 // Any K, any alignment: one element per lane per step.
 template <typename T>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_elem_kernel(KtDeviceTables tb, int64_t tile0,
@@ -185,8 +271,12 @@ hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntile
                           bool vector_ok, hipStream_t s)
 {
     dim3 grid((unsigned)ntiles), block(KT_BLOCK);
-    if (!vector_ok || K > 8) {
+    if (!vector_ok) {
         kt_fused_elem_kernel<T><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
+        return hipGetLastError();
+    }
+    if (K > 8) {
+        kt_fused_manyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
         return hipGetLastError();
     }
     switch (K) {

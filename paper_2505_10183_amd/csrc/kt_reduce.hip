@@ -75,14 +75,15 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
     }
 }
 
-// Any K (weights in the kernel argument block), 16-byte vectors.
+// K > 8: peers in chunks, accumulators in registers across chunks (sum_in_chunks).
 template <typename T>
-__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_anyk_kernel(KtDeviceTables tb, int64_t tile0,
-                                                                  const void *const *peer_ptrs, int K,
-                                                                  KtWeights wts, void *const *out_ptrs)
+__global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTables tb, int64_t tile0,
+                                                                   const void *const *peer_ptrs, int K,
+                                                                   KtWeights wts, void *const *out_ptrs)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
     const KtTile tl = tb.tiles[tile0 + blockIdx.x];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const int tid = threadIdx.x;
@@ -90,6 +91,14 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_anyk_kernel(KtDeviceTables
     T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
     const int64_t n = g.end - g.start;
     const int nvec = (int)(n / VE);
+    if (nvec == KT_TILE_VECS) {
+        Acc<T> acc[VPT];
+        sum_in_chunks<T>(acc, [&](int k) { return reinterpret_cast<const T *>(pp[k]) + g.start; }, wts, K, tid);
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc[u].finish());
+        return;
+    }
+    // the ragged last tile of a bucket: one vector at a time
     for (int v = tid; v < nvec; v += KT_BLOCK) {
         Acc<T> acc;
         acc.first(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[0]) + g.start) + v), wts.w[0]);
@@ -140,7 +149,7 @@ hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntil
     case KK: kt_reduce_kernel<T, KK><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
         KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
-    default: kt_reduce_anyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
+    default: kt_reduce_manyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
     }
     return hipGetLastError();
 }

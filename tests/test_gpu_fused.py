@@ -84,7 +84,7 @@ def run_case(w, align, scale, in_place=False, misalign=False, batched=True):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 7, 8, 9])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 7, 8, 9, 13, 16, 23])
 def test_fused_vs_checker_and_chained(dtype, K):
     w = wl.ragged_workload(dtype=dtype, K=K, seed=60 + K)
     run_case(w, 16, 1.0)

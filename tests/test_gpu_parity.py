@@ -254,7 +254,7 @@ def run_reduce(plan, peers, weights, outs=None, bucket=-1):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8, 9, 16])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 5, 6, 7, 8, 9, 13, 16, 23])
 def test_reduce_vs_checker(dtype, K):
     w = wl.ragged_workload(dtype=dtype, K=K, seed=30 + K)
     plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
