@@ -334,12 +334,12 @@ static kt_status stage_pointers(kt_plan *p, const uint64_t *vals, size_t n, hipS
         if (victim->dev) (void)hipFree(victim->dev);
         if (victim->pinned) (void)hipHostFree(victim->pinned);
         victim->dev = nullptr; victim->pinned = nullptr; victim->cap = 0;
-        const size_t cap = n < 64 ? 64 : n;
-        e = hipMalloc(&victim->dev, cap * 8);
+        const size_t entries = n < 64 ? 64 : n;
+        e = hipMalloc(&victim->dev, entries * 8);
         if (e != hipSuccess) return hip_fail("hipMalloc(pointer table)", e);
-        e = hipHostMalloc(reinterpret_cast<void **>(&victim->pinned), cap * 8, hipHostMallocDefault);
+        e = hipHostMalloc(reinterpret_cast<void **>(&victim->pinned), entries * 8, hipHostMallocDefault);
         if (e != hipSuccess) { (void)hipFree(victim->dev); victim->dev = nullptr; return hip_fail("hipHostMalloc(pointer table)", e); }
-        victim->cap = cap;
+        victim->cap = entries;
     }
     if (!victim->uploaded) {
         e = hipEventCreateWithFlags(&victim->uploaded, hipEventDisableTiming);
