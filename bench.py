@@ -475,6 +475,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
         binding.LIB_PATH = os.path.abspath(path)
         libs[name] = binding.lib()
         plans[name] = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
+        plans[name].kt_plan_set_weights(st["a_w"])
     td = st["local"][0].dtype
     elems = st["plan"].bucket_elems()
     flat_l = [torch.empty(n, dtype=td, device=dev).normal_(0, w.sigma) for n in elems]
@@ -512,6 +513,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
             "pack": (lambda: p.kt_bucket_pack(-1, a_l, a_s0), 2 * s),
             "pack_views": (lambda: p.kt_bucket_pack(-1, a_vl, a_s0), 2 * s),
             "reduce": (lambda: p.kt_weighted_reduce(-1, a_pe, K, a_w, a_o), (K + 1) * s),
+            "reduce_resident_weights": (lambda: p.kt_weighted_reduce(-1, a_pe, K, None, a_o), (K + 1) * s),
             "unpack": (lambda: p.kt_bucket_unpack_scale(-1, a_o, 1.0, a_r), 2 * s),
             "unpack_views": (lambda: p.kt_bucket_unpack_scale(-1, a_o, 1.0, a_vo), 2 * s),
             "step": (batched, (K + 5) * s),

@@ -41,7 +41,8 @@
  *    weights, scale, lr, momentum, weight_decay and first_step.  After new
  *    shares (kt_replan_shares) or a learning-rate change a replayed graph
  *    still applies the old values: record the step again, or update the
- *    kernel node's parameters.  A recorded first_step != 0 would reset the
+ *    kernel node's parameters.  For the weights there is a third way: record
+ *    the calls with weights == NULL and change them with kt_plan_set_weights.  A recorded first_step != 0 would reset the
  *    momentum on every replay, so kt_bucket_unpack_sgd refuses it under
  *    capture (KT_EUNSUPPORTED).
  *  - Streams passed to device calls should outlive the plan.  If the stream of
@@ -258,7 +259,8 @@ KT_API kt_status kt_bucket_pack(kt_plan *plan, int bucket,
  *   peer_bufs  host, in: device pointers, entry [b * K + k] = peer k's copy of
  *                        bucket b (num_buckets * K entries).
  *   K          in      : 1 <= K <= KT_MAX_PEERS.
- *   weights    host, in: K binary32 weights (copied during the call).
+ *   weights    host, in: K binary32 weights (copied during the call), or NULL
+ *                        for the weights set with kt_plan_set_weights.
  *   out_bufs   host, in: device pointers by bucket.  out_b may be identical to
  *                        one peer_{b,k} (in place); any other overlap is an
  *                        error where detected (equal ranges are; partial
@@ -268,6 +270,25 @@ KT_API kt_status kt_weighted_reduce(kt_plan *plan, int bucket,
                              const void *const *peer_bufs, int K,
                              const float *weights, void *const *out_bufs,
                              void *stream);
+
+/*
+ * Device-resident weights, for recorded graphs that must follow new shares
+ * (Sec. III-C phase 1, online adaptation).  kt_plan_set_weights copies K weights
+ * into device memory owned by the plan, on `stream`, ordered behind the work
+ * already enqueued there.  kt_weighted_reduce, kt_fused_step and
+ * kt_fused_step_noalloc called with weights == NULL read these K weights from
+ * device memory when their kernel runs, instead of freezing K values into the
+ * launch: a graph recorded with weights == NULL applies, on every replay,
+ * whatever the last kt_plan_set_weights on the replaying stream (or one
+ * synchronised with it) has written.  The arithmetic is the same.
+ *
+ *   weights host, in: K binary32 weights (copied before the call returns).
+ * Errors: KT_EINVAL (arguments); KT_EUNSUPPORTED under stream capture (the
+ * copy cannot be recorded; call it outside capture); a device call with
+ * weights == NULL fails with KT_EINVAL if no weights were set or K differs.
+ */
+KT_API kt_status kt_plan_set_weights(kt_plan *plan, const float *weights, int K,
+                                     void *stream);
 
 /*
  * Unpack with scale: tensor_t[i] = scale * bucket_b[off_t + i] for every

@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd_master.argtypes = [vp, i32, c.POINTER(vp), c.c_float, c.POINTER(vp), c.POINTER(vp),
                                                   c.POINTER(vp), c.c_float, c.c_float, c.c_float, i32, vp]
         L.kt_bucket_unpack_sgd_master.restype = i32
+        L.kt_plan_set_weights.argtypes = [vp, c.POINTER(c.c_float), i32, vp]
+        L.kt_plan_set_weights.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -248,11 +250,19 @@ class Plan:
         return items if pre else _ptr_array(items)
 
     def _weights(self, weights, K: int):
+        if weights is None:         # the plan's device-resident weights (kt_plan_set_weights)
+            return None
         if len(weights) != K:
             raise ValueError("need K = %d weights, got %d" % (K, len(weights)))
         if isinstance(weights, ctypes.Array):
             return weights
         return (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
+
+    def kt_plan_set_weights(self, weights, stream=None):
+        """Copy the weights into the plan's device memory; device calls with weights=None read them there."""
+        K = len(weights)
+        w = weights if isinstance(weights, ctypes.Array) else (ctypes.c_float * max(1, K))(*[float(x) for x in weights])
+        _check(lib().kt_plan_set_weights(self._h, w, K, _stream(stream)))
 
     def kt_bucket_pack(self, bucket: int, tensors, bucket_bufs, stream=None):
         T, nb = len(self.numels), self.num_buckets

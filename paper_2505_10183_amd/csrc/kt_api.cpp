@@ -109,6 +109,7 @@ struct Tick {
 static const int KT_SLOTS = 8;
 static const int KT_TICKS = 16;
 static const uint64_t KT_TICK_EVERY = 4;
+static const int KT_WSTAGE = 4;
 
 struct kt_plan {
     KtHostPlan hp;
@@ -122,6 +123,13 @@ struct kt_plan {
     // (so that eager calls keep all KT_SLOTS tables) and kept until the plan
     // is destroyed, because a graph may be replayed at any time.
     std::vector<PtrSlot *> graph_tables;
+    // device-resident weights (kt_plan_set_weights): one array of KT_MAX_PEERS floats on the
+    // device, a small ring of pinned staging copies so that successive updates do not wait
+    float *dev_w = nullptr;
+    int dev_w_K = 0;
+    float *w_stage = nullptr;                 // KT_WSTAGE * KT_MAX_PEERS floats, pinned
+    hipEvent_t w_done[4] = {nullptr, nullptr, nullptr, nullptr};
+    int w_head = 0;
     Tick ticks[KT_TICKS];
     int tick_head = 0;
     uint64_t seq = 0;      // launches issued through this plan
@@ -169,6 +177,10 @@ extern "C" kt_status kt_plan_destroy(kt_plan *p)
         for (PtrSlot *g : p->graph_tables) { release_slot(*g); delete g; }
         for (Tick &t : p->ticks)
             if (t.ev) (void)hipEventDestroy(t.ev);
+        if (p->dev_w) (void)hipFree(p->dev_w);
+        if (p->w_stage) (void)hipHostFree(p->w_stage);
+        for (hipEvent_t ev : p->w_done)
+            if (ev) (void)hipEventDestroy(ev);
         if (p->dev_blob) (void)hipFree(p->dev_blob);
         if (cur != p->device && cur >= 0) (void)hipSetDevice(cur);
     }
@@ -406,6 +418,21 @@ static kt_status select(const kt_plan *p, int bucket, const char *who, int *b0, 
     return KT_OK;
 }
 
+// The weights of a launch: the caller's K values by value, or (weights == NULL) the plan's
+// device-resident ones.  Host-only check.
+static kt_status resolve_weights(const kt_plan *p, const float *weights, int K, const char *who, KtWeights *w)
+{
+    memset(w, 0, sizeof *w);
+    if (weights) {
+        for (int k = 0; k < K; ++k) w->w[k] = weights[k];
+        return KT_OK;
+    }
+    if (!p->dev_w) { kt_set_error("%s: NULL weights and no weights set with kt_plan_set_weights", who); return KT_EINVAL; }
+    if (p->dev_w_K != K) { kt_set_error("%s: K=%d but the plan's resident weights are for K=%d", who, K, p->dev_w_K); return KT_EINVAL; }
+    w->dev = p->dev_w;
+    return KT_OK;
+}
+
 // Shared by pack and unpack: validate, build [tensor ptrs | bucket ptrs], stage.
 static kt_status prepare_tensor_call(kt_plan *p, int bucket, const void *const *tensor_ptrs,
                                      const void *const *bucket_bufs, const char *who, hipStream_t stream,
@@ -496,12 +523,14 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     const char *who = "kt_weighted_reduce";
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
-    if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
     std::lock_guard<std::mutex> lock(p->mu);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    KtWeights w;
+    kt_status st = resolve_weights(p, weights, K, who, &w);
+    if (st != KT_OK) return st;
     int b0, b1;
     int64_t tile0, ntiles;
-    kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
+    st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
     if (st != KT_OK || ntiles == 0) return st;
     if (!peer_bufs || !out_bufs) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
     const KtHostPlan &hp = p->hp;
@@ -529,9 +558,6 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
             }
         }
     }
-    KtWeights w;
-    memset(&w, 0, sizeof w);
-    for (int k = 0; k < K; ++k) w.w[k] = weights[k];
     st = ensure_device(p, s);
     if (st != KT_OK) return st;
     PtrSlot *slot = nullptr;
@@ -545,6 +571,53 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     KT_GUARD_END("kt_weighted_reduce")
 }
 
+extern "C" kt_status kt_plan_set_weights(kt_plan *p, const float *weights, int K, void *stream)
+{
+    KT_GUARD_BEGIN
+    const char *who = "kt_plan_set_weights";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
+    if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (capturing(s)) {
+        kt_set_error("%s: the upload cannot be recorded into a graph; call it outside stream capture, on the stream "
+                     "that replays the graph", who);
+        return KT_EUNSUPPORTED;
+    }
+    kt_status st = ensure_device(p, s);
+    if (st != KT_OK) return st;
+    hipError_t e;
+    if (!p->dev_w) {
+        void *d = nullptr, *h = nullptr;
+        e = hipMalloc(&d, KT_MAX_PEERS * sizeof(float));
+        if (e != hipSuccess) return hip_fail("hipMalloc(weights)", e);
+        e = hipHostMalloc(&h, KT_WSTAGE * KT_MAX_PEERS * sizeof(float), hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipFree(d); return hip_fail("hipHostMalloc(weights)", e); }
+        p->dev_w = static_cast<float *>(d);
+        p->w_stage = static_cast<float *>(h);
+    }
+    const int i = p->w_head;
+    p->w_head = (i + 1) % KT_WSTAGE;
+    if (!p->w_done[i]) {
+        e = hipEventCreateWithFlags(&p->w_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+    } else {
+        e = hipEventSynchronize(p->w_done[i]);        // the upload that last used this staging copy
+        if (e != hipSuccess) return hip_fail("hipEventSynchronize", e);
+    }
+    float *stage = p->w_stage + (size_t)i * KT_MAX_PEERS;
+    memset(stage, 0, KT_MAX_PEERS * sizeof(float));
+    memcpy(stage, weights, (size_t)K * sizeof(float));
+    e = hipMemcpyAsync(p->dev_w, stage, KT_MAX_PEERS * sizeof(float), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail("hipMemcpyAsync(weights)", e);
+    e = hipEventRecord(p->w_done[i], s);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    p->dev_w_K = K;
+    return KT_OK;
+    KT_GUARD_END("kt_plan_set_weights")
+}
+
 kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
                            const void *const *peer_bufs, int K, const float *weights,
                            void *const *out_tensor_ptrs, const char *who, std::vector<uint64_t> &vals,
@@ -553,9 +626,10 @@ kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *loca
     *ntiles = 0;
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
     if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
-    if (!weights) { kt_set_error("%s: NULL weights", who); return KT_EINVAL; }
+    kt_status st = resolve_weights(p, weights, K, who, w);
+    if (st != KT_OK) return st;
     int b0, b1;
-    kt_status st = select(p, bucket, who, &b0, &b1, tile0, ntiles);
+    st = select(p, bucket, who, &b0, &b1, tile0, ntiles);
     if (st != KT_OK || *ntiles == 0) return st;
     if (!local_tensor_ptrs || !out_tensor_ptrs || (K > 1 && !peer_bufs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
     const KtHostPlan &hp = p->hp;
@@ -590,8 +664,6 @@ kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *loca
             }
         }
     }
-    memset(w, 0, sizeof *w);
-    for (int k = 0; k < K; ++k) w->w[k] = weights[k];
     *vector_ok = vec;
     return KT_OK;
 }

@@ -174,6 +174,16 @@ __device__ __forceinline__ GlobalView global_view(const KtDeviceTables &tb, cons
     return v;
 }
 
+// Weight of peer k: from the kernel-argument block, or, when the caller asked for
+// the plan's device-resident weights, from device memory (uniform scalar reads).
+// (a template parameter, so that launches with weights by value run exactly the code they
+// would without this choice.)
+template <bool DEVW> __device__ __forceinline__ float kt_weight(const KtWeights &wts, int k)
+{
+    if (DEVW) return wts.dev[k];
+    return wts.w[k];
+}
+
 // ---- weighted sum of one 16-byte vector per peer ---------------------------
 // Per element: acc = w0*x0 (rounded), then acc = fma(wk, xk, acc), ascending k.
 
@@ -236,7 +246,7 @@ template <typename T> struct Chunk;
 template <> struct Chunk<float> { static constexpr int N = 8; };       // 148 VGPRs, 3 waves per SIMD
 template <> struct Chunk<uint16_t> { static constexpr int N = 6; };    // 8 accumulators per vector: 6 keeps 3 waves per SIMD
 
-template <typename T, int KC, typename P>
+template <typename T, int KC, bool DEVW, typename P>
 __device__ __forceinline__ void sum_chunk(Acc<T> *acc, P ptr, const KtWeights &wts, int k0, int tid)
 {
     constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
@@ -249,7 +259,7 @@ __device__ __forceinline__ void sum_chunk(Acc<T> *acc, P ptr, const KtWeights &w
     }
 #pragma unroll
     for (int j = 0; j < KC; ++j) {
-        const float w = wts.w[k0 + j];
+        const float w = kt_weight<DEVW>(wts, k0 + j);
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             if (j == 0 && k0 == 0) acc[u].first(r[u][j], w); else acc[u].add(r[u][j], w);
@@ -258,21 +268,21 @@ __device__ __forceinline__ void sum_chunk(Acc<T> *acc, P ptr, const KtWeights &w
 }
 
 // acc[u] = sum over all K peers of vector u of a full tile.
-template <typename T, typename P>
+template <typename T, bool DEVW, typename P>
 __device__ __forceinline__ void sum_in_chunks(Acc<T> *acc, P ptr, const KtWeights &wts, int K, int tid)
 {
     constexpr int CH = Chunk<T>::N;
     int k0 = 0;
 #pragma unroll 1
-    for (; k0 + CH <= K; k0 += CH) sum_chunk<T, CH>(acc, ptr, wts, k0, tid);
+    for (; k0 + CH <= K; k0 += CH) sum_chunk<T, CH, DEVW>(acc, ptr, wts, k0, tid);
     switch (K - k0) {      // the last, shorter chunk (uniform over the grid)
-    case 1: sum_chunk<T, 1>(acc, ptr, wts, k0, tid); break;
-    case 2: sum_chunk<T, 2>(acc, ptr, wts, k0, tid); break;
-    case 3: sum_chunk<T, 3>(acc, ptr, wts, k0, tid); break;
-    case 4: sum_chunk<T, 4>(acc, ptr, wts, k0, tid); break;
-    case 5: sum_chunk<T, 5>(acc, ptr, wts, k0, tid); break;
-    case 6: if (CH > 6) sum_chunk<T, 6>(acc, ptr, wts, k0, tid); break;
-    case 7: if (CH > 7) sum_chunk<T, 7>(acc, ptr, wts, k0, tid); break;
+    case 1: sum_chunk<T, 1, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 2: sum_chunk<T, 2, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 3: sum_chunk<T, 3, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 4: sum_chunk<T, 4, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 5: sum_chunk<T, 5, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 6: if (CH > 6) sum_chunk<T, 6, DEVW>(acc, ptr, wts, k0, tid); break;
+    case 7: if (CH > 7) sum_chunk<T, 7, DEVW>(acc, ptr, wts, k0, tid); break;
     default: break;
     }
 }

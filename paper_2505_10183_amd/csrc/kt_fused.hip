@@ -79,7 +79,7 @@ __device__ __forceinline__ void fused_mixed(const V &tv, int nt, const TileGeom 
     }
 }
 
-template <typename T, int K>
+template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, int64_t tile0,
                                                             const void *const *local_ptrs,
                                                             const void *const *peer_ptrs, KtWeights wts,
@@ -101,7 +101,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
         x[k - 1] = reinterpret_cast<const T *>(peer_ptrs[(int64_t)g.bucket * (K - 1) + (k - 1)]) + g.start;
     float w[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) w[k] = wts.w[k];
+    for (int k = 0; k < K; ++k) w[k] = kt_weight<DEVW>(wts, k);
 
     if (tl.nt == 0) {
         const int64_t rel = g.start - tb.t_off[tl.t0];
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
 // K > 8, 16-byte vectors: full solid tiles take the peers in chunks with the
 // accumulators in registers (sum_in_chunks; peer 0 is the local tensor); every
 // other tile goes vector by vector with a loop over the peers.
-template <typename T, typename V>
+template <typename T, bool DEVW, typename V>
 __device__ __forceinline__ void fused_mixed_manyk(const V &tv, int nt, const TileGeom &g, int64_t b_n,
                                                   const void *const *pp, int K, const KtWeights &wts, float scale)
 {
@@ -173,10 +173,10 @@ __device__ __forceinline__ void fused_mixed_manyk(const V &tv, int nt, const Til
                 const uintptr_t pd = tv.ptr2[i] + (uintptr_t)r * sizeof(T);
                 if (((ps | pd) & 15u) == 0) {
                     Acc<T> acc;
-                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), wts.w[0]);
+                    acc.first(ld_vec(reinterpret_cast<const void *>(ps)), kt_weight<DEVW>(wts, 0));
 #pragma unroll 4
                     for (int k = 1; k < K; ++k)
-                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k - 1]) + g.start) + v), wts.w[k]);
+                        acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k - 1]) + g.start) + v), kt_weight<DEVW>(wts, k));
                     st_vec(reinterpret_cast<void *>(pd), scale_vec<T>(acc.finish(), scale));
                     continue;
                 }
@@ -189,15 +189,15 @@ __device__ __forceinline__ void fused_mixed_manyk(const V &tv, int nt, const Til
             while (i + 1 < nt && tv.off[i + 1] <= e) ++i;
             if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
                 const int64_t r = e - tv.off[i];
-                float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
-                for (int k = 1; k < K; ++k) a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
+                float a = __fmul_rn(kt_weight<DEVW>(wts, 0), widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
+                for (int k = 1; k < K; ++k) a = __fmaf_rn(kt_weight<DEVW>(wts, k), widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
                 st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
             }
         }
     }
 }
 
-template <typename T>
+template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables tb, int64_t tile0,
                                                                   const void *const *local_ptrs,
                                                                   const void *const *peer_ptrs, int K,
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables
         T *dst = reinterpret_cast<T *>(out_ptrs[tl.t0]) + rel;
         if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0) {
             Acc<T> acc[VPT];
-            sum_in_chunks<T>(acc, [&](int k) { return k == 0 ? src : reinterpret_cast<const T *>(pp[k - 1]) + g.start; },
+            sum_in_chunks<T, DEVW>(acc, [&](int k) { return k == 0 ? src : reinterpret_cast<const T *>(pp[k - 1]) + g.start; },
                              wts, K, tid);
 #pragma unroll
             for (int u = 0; u < VPT; ++u)
@@ -232,15 +232,15 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables
     const void *const *op = reinterpret_cast<const void *const *>(out_ptrs);
     if (nt <= KT_LDS_TENSORS) {
         const LdsView tv = stage_lds(lds, tb, local_ptrs, op, tl.t0, nt);
-        fused_mixed_manyk<T>(tv, nt, g, b_n, pp, K, wts, scale);
+        fused_mixed_manyk<T, DEVW>(tv, nt, g, b_n, pp, K, wts, scale);
     } else {
         const GlobalView tv = global_view(tb, local_ptrs, op, tl.t0);
-        fused_mixed_manyk<T>(tv, nt, g, b_n, pp, K, wts, scale);
+        fused_mixed_manyk<T, DEVW>(tv, nt, g, b_n, pp, K, wts, scale);
     }
 }
 
 // Any K, any alignment: one element per lane per step.
-template <typename T>
+template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_elem_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *local_ptrs,
                                                                  const void *const *peer_ptrs, int K,
@@ -257,31 +257,31 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_elem_kernel(KtDeviceTables 
         const int i = find_owner_v(tv, nt, e);
         if (i >= 0 && e - tv.off[i] < tv.numel[i]) {
             const int64_t r = e - tv.off[i];
-            float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
+            float a = __fmul_rn(kt_weight<DEVW>(wts, 0), widen(ld_elem(reinterpret_cast<const T *>(tv.ptr[i]) + r)));
             for (int k = 1; k < K; ++k)
-                a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
+                a = __fmaf_rn(kt_weight<DEVW>(wts, k), widen(ld_elem(reinterpret_cast<const T *>(pp[k - 1]) + e)), a);
             st_elem(reinterpret_cast<T *>(tv.ptr2[i]) + r, scale_elem(narrow<T>(a), scale));
         }
     }
 }
 
-template <typename T>
+template <typename T, bool DEVW>
 hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntiles, const void *const *locals,
                           const void *const *peers, int K, const KtWeights &w, float scale, void *const *outs,
                           bool vector_ok, hipStream_t s)
 {
     dim3 grid((unsigned)ntiles), block(KT_BLOCK);
     if (!vector_ok) {
-        kt_fused_elem_kernel<T><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
+        kt_fused_elem_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
         return hipGetLastError();
     }
     if (K > 8) {
-        kt_fused_manyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
+        kt_fused_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
         return hipGetLastError();
     }
     switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_fused_kernel<T, KK><<<grid, block, 0, s>>>(tb, tile0, locals, peers, w, scale, outs); break;
+    case KK: kt_fused_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, w, scale, outs); break;
         KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
     default: return hipErrorInvalidValue;
@@ -296,7 +296,9 @@ int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64_
                     float scale, void *const *d_out_ptrs, bool vector_ok, void *stream)
 {
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (dt == KT_F32)
-        return (int)launch_fused_t<float>(tb, tile0, ntiles, d_local_ptrs, d_peer_ptrs, K, w, scale, d_out_ptrs, vector_ok, s);
-    return (int)launch_fused_t<uint16_t>(tb, tile0, ntiles, d_local_ptrs, d_peer_ptrs, K, w, scale, d_out_ptrs, vector_ok, s);
+#define KT_FUSED(TT, DD) \
+    (int)launch_fused_t<TT, DD>(tb, tile0, ntiles, d_local_ptrs, d_peer_ptrs, K, w, scale, d_out_ptrs, vector_ok, s)
+    if (dt == KT_F32) return w.dev ? KT_FUSED(float, true) : KT_FUSED(float, false);
+    return w.dev ? KT_FUSED(uint16_t, true) : KT_FUSED(uint16_t, false);
+#undef KT_FUSED
 }

@@ -69,8 +69,12 @@ int kt_launch_unpack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                      int64_t ntiles, const void *const *d_bucket_ptrs,
                      float scale, void *const *d_tensor_ptrs, bool vector_ok,
                      void *stream);
+// The K weights of a launch travel in the kernel-argument block (`w`), unless
+// `dev` is set: then the kernels read them from that device array when they
+// run (kt_plan_set_weights), so that a recorded graph follows later updates.
 struct KtWeights {
     float w[KT_MAX_PEERS];
+    const float *dev;
 };
 int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                      int64_t ntiles, const void *const *d_peer_ptrs, int K,

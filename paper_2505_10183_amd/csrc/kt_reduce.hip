@@ -14,7 +14,7 @@
 
 namespace {
 
-template <typename T, int K>
+template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
                                                              const void *const *peer_ptrs, KtWeights wts,
                                                              void *const *out_ptrs)
@@ -33,7 +33,7 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
     T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]) + g.start;
     float w[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) w[k] = wts.w[k];
+    for (int k = 0; k < K; ++k) w[k] = kt_weight<DEVW>(wts, k);
 
     const int64_t n = g.end - g.start;
     const int nvec = (int)(n / VE);
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
 }
 
 // K > 8: peers in chunks, accumulators in registers across chunks (sum_in_chunks).
-template <typename T>
+template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTables tb, int64_t tile0,
                                                                    const void *const *peer_ptrs, int K,
                                                                    KtWeights wts, void *const *out_ptrs)
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTable
     const int nvec = (int)(n / VE);
     if (nvec == KT_TILE_VECS) {
         Acc<T> acc[VPT];
-        sum_in_chunks<T>(acc, [&](int k) { return reinterpret_cast<const T *>(pp[k]) + g.start; }, wts, K, tid);
+        sum_in_chunks<T, DEVW>(acc, [&](int k) { return reinterpret_cast<const T *>(pp[k]) + g.start; }, wts, K, tid);
 #pragma unroll
         for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc[u].finish());
         return;
@@ -101,23 +101,23 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTable
     // the ragged last tile of a bucket: one vector at a time
     for (int v = tid; v < nvec; v += KT_BLOCK) {
         Acc<T> acc;
-        acc.first(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[0]) + g.start) + v), wts.w[0]);
+        acc.first(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[0]) + g.start) + v), kt_weight<DEVW>(wts, 0));
 #pragma unroll 4
         for (int k = 1; k < K; ++k)
-            acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k]) + g.start) + v), wts.w[k]);
+            acc.add(ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k]) + g.start) + v), kt_weight<DEVW>(wts, k));
         st_vec(reinterpret_cast<u32x4 *>(out) + v, acc.finish());
     }
     const int64_t e = (int64_t)nvec * VE + tid;
     if (e < n) {
-        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + g.start + e)));
+        float a = __fmul_rn(kt_weight<DEVW>(wts, 0), widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + g.start + e)));
         for (int k = 1; k < K; ++k)
-            a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + g.start + e)), a);
+            a = __fmaf_rn(kt_weight<DEVW>(wts, k), widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + g.start + e)), a);
         st_elem(out + e, narrow<T>(a));
     }
 }
 
 // Any K, any alignment: one element per lane per step.
-template <typename T>
+template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_elem_kernel(KtDeviceTables tb, int64_t tile0,
                                                                   const void *const *peer_ptrs, int K,
                                                                   KtWeights wts, void *const *out_ptrs)
@@ -129,27 +129,27 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_elem_kernel(KtDeviceTables
     const void *const *pp = peer_ptrs + (int64_t)g.bucket * K;
     T *out = reinterpret_cast<T *>(out_ptrs[g.bucket]);
     for (int64_t e = g.start + threadIdx.x; e < g.end; e += KT_BLOCK) {
-        float a = __fmul_rn(wts.w[0], widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + e)));
-        for (int k = 1; k < K; ++k) a = __fmaf_rn(wts.w[k], widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + e)), a);
+        float a = __fmul_rn(kt_weight<DEVW>(wts, 0), widen(ld_elem(reinterpret_cast<const T *>(pp[0]) + e)));
+        for (int k = 1; k < K; ++k) a = __fmaf_rn(kt_weight<DEVW>(wts, k), widen(ld_elem(reinterpret_cast<const T *>(pp[k]) + e)), a);
         st_elem(out + e, narrow<T>(a));
     }
 }
 
-template <typename T>
+template <typename T, bool DEVW>
 hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntiles, const void *const *peers,
                            int K, const KtWeights &w, void *const *outs, bool vector_ok, hipStream_t s)
 {
     dim3 grid((unsigned)ntiles), block(KT_BLOCK);
     if (!vector_ok) {
-        kt_reduce_elem_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs);
+        kt_reduce_elem_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs);
         return hipGetLastError();
     }
     switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_reduce_kernel<T, KK><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
+    case KK: kt_reduce_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
         KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
-    default: kt_reduce_manyk_kernel<T><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
+    default: kt_reduce_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
     }
     return hipGetLastError();
 }
@@ -161,6 +161,10 @@ int kt_launch_reduce(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, int64
                      bool vector_ok, void *stream)
 {
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
-    if (dt == KT_F32) return (int)launch_reduce_t<float>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
-    return (int)launch_reduce_t<uint16_t>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s);
+    // weights by value (the usual case) and weights read from device memory are separate instantiations
+    if (dt == KT_F32)
+        return (int)(w.dev ? launch_reduce_t<float, true>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s)
+                           : launch_reduce_t<float, false>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s));
+    return (int)(w.dev ? launch_reduce_t<uint16_t, true>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s)
+                       : launch_reduce_t<uint16_t, false>(tb, tile0, ntiles, d_peer_ptrs, K, w, d_out_ptrs, vector_ok, s));
 }

@@ -233,3 +233,79 @@ def test_recorded_weights_are_frozen_until_the_step_is_recorded_again():
         for t in range(len(w.numels)):
             assert raw(host(params[t])).tobytes() == raw(hp_[t]).tobytes(), (r, t)
             assert raw(host(moms[t])).tobytes() == raw(hv_[t]).tobytes(), (r, t)
+
+
+def test_recorded_step_follows_resident_weights():
+    """Calls recorded with weights=None read the plan's device-resident weights
+    when they run: after new shares, kt_plan_set_weights on the replaying stream
+    is enough, the graph is not recorded again.  Chained reduce and fused pass."""
+    K = 4
+    w = wl.ragged_workload(dtype="bf16", K=K, seed=78, n_tensors=30)
+    plan = kt.Plan(w.numels, "bf16", w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    grads = [wl.gradient_set(w, k, DEV) for k in range(K)]
+    peers = [[torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in plan.bucket_elems()] for _ in range(K)]
+    for k in range(K):
+        plan.kt_bucket_pack(-1, grads[k], peers[k])
+    flat = [peers[k][b] for b in range(nb) for k in range(K)]
+    others = [peers[k][b] for b in range(nb) for k in range(1, K)]
+    outs = [torch.empty_like(t) for t in peers[0]]
+    res = [torch.empty_like(t) for t in grads[0]]
+    B = 128
+    shares, w_now = kt.kt_plan_shares([1.0, 0.8, 0.5, 0.5], B)
+    hp = [[host(peers[k][b]) for k in range(K)] for b in range(nb)]
+    hg = [[host(t) for t in g] for g in grads]
+
+    def check(wts, tag):
+        torch.cuda.synchronize()
+        wv = np.array(wts, np.float32)
+        for b in range(nb):
+            want = oracle.weighted_reduce(hp[b], wv, "bf16", "S")
+            assert host(outs[b]).tobytes() == want.tobytes(), (tag, "reduce", b)
+        ref = oracle.direct(hg, wv, 0.5, "bf16", "S")
+        for t in range(len(w.numels)):
+            assert host(res[t]).tobytes() == ref[t].tobytes(), (tag, "fused", t)
+
+    def step():
+        plan.kt_weighted_reduce(-1, flat, K, None, outs)
+        plan.kt_fused_step(-1, grads[0], others, K, None, 0.5, res)
+
+    with pytest.raises(kt.KtError):
+        step()                                    # no resident weights yet
+    plan.kt_plan_set_weights(w_now)
+    step()                                        # eager: tables resident, resident weights read
+    check(w_now, "eager")
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    ema = [0.0] * K
+    speed = np.array([1.0, 0.8, 0.5, 0.5])
+    for r in range(4):
+        # a device slows down; re-plan; push the new weights; replay the same graph
+        speed[r % K] *= 0.6
+        times = [float(b / s_) for b, s_ in zip(shares, speed)]
+        ema, shares, w_now = kt.kt_replan_shares(times, shares, ema, 1.0, B)
+        plan.kt_plan_set_weights(w_now)
+        for t in outs + res:
+            t.zero_()
+        g.replay()
+        check(w_now, "replay %d" % r)
+    # weights given by value still work beside the resident ones, and K must match them
+    plan.kt_weighted_reduce(-1, flat, K, [0.25] * K, outs)
+    plan.kt_fused_step(-1, grads[0], others, K, [0.25] * K, 0.5, res)
+    check([0.25] * K, "by value")
+    with pytest.raises(kt.KtError):
+        plan.kt_weighted_reduce(-1, flat[:nb * 3], 3, None, outs)
+    # the upload itself cannot be recorded
+    s = torch.cuda.Stream()
+    g2 = torch.cuda.CUDAGraph()
+    err = None
+    with torch.cuda.stream(s):
+        g2.capture_begin()
+        try:
+            plan.kt_plan_set_weights(w_now)
+        except kt.KtError as e:
+            err = e
+        g2.capture_end()
+    assert err is not None and err.status_name == "KT_EUNSUPPORTED"
+

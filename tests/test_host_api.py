@@ -335,6 +335,23 @@ def test_replan_errors_leave_state_untouched():
     assert L.kt_replan_shares(t2, u, e, 0.5, 2, 8, b, None) == 0 and sum(b) == 8
 
 
+def test_resident_weights_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    L = kt.binding.lib()
+    w2 = (ctypes.c_float * 2)(0.5, 0.5)
+    assert L.kt_plan_set_weights(None, w2, 2, None) == 1
+    assert L.kt_plan_set_weights(p._h, None, 2, None) == 1
+    assert L.kt_plan_set_weights(p._h, w2, 0, None) == 1
+    assert L.kt_plan_set_weights(p._h, w2, 65, None) == 1
+    # device calls without weights need resident ones
+    with pytest.raises(kt.KtError) as ei:
+        p.kt_weighted_reduce(-1, [4096, 8192], 2, None, [16384], stream=0)
+    assert ei.value.status_name == "KT_EINVAL" and "kt_plan_set_weights" in str(ei.value)
+    with pytest.raises(kt.KtError) as ei:
+        p.kt_fused_step(-1, [16, 1600], [4096], 2, None, 1.0, [32000, 48000], stream=0)
+    assert ei.value.status_name == "KT_EINVAL"
+
+
 def test_unpack_sgd_master_argument_errors_without_gpu():
     p = kt.Plan([10, 20], "bf16", 0, 16)
     ok_p, ok_v, ok_m, ok_b = [16000, 32000], [48000, 64000], [80000, 96000], [4096]
