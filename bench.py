@@ -476,6 +476,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
         libs[name] = binding.lib()
         plans[name] = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
         plans[name].kt_plan_set_weights(st["a_w"])
+        plans[name].kt_plan_set_sgd(1.0, 0.1, 0.9, 5e-4)
     td = st["local"][0].dtype
     elems = st["plan"].bucket_elems()
     flat_l = [torch.empty(n, dtype=td, device=dev).normal_(0, w.sigma) for n in elems]
@@ -526,6 +527,7 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
             "sgd": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False), s + 16),
             "sgd_master": (lambda: p.kt_bucket_unpack_sgd_master(-1, a_o, 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4, False), s + 18),
             "sgd_views": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_vp, a_vv, 0.1, 0.9, 5e-4, False), s + 16),
+            "sgd_resident_scalars": (lambda: p.kt_bucket_unpack_sgd_resident(-1, a_o, a_p, a_v, None, False), s + 16),
         }
 
     def timeit(fn):
@@ -568,7 +570,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="decoder_1p3b")
     ap.add_argument("--also", default="vit_b16,resnet18,mobilenetv2,mlp",
                     help="comma list of further workloads reported for context (the three small ones are "

@@ -41,10 +41,12 @@
  *    weights, scale, lr, momentum, weight_decay and first_step.  After new
  *    shares (kt_replan_shares) or a learning-rate change a replayed graph
  *    still applies the old values: record the step again, or update the
- *    kernel node's parameters.  For the weights there is a third way: record
- *    the calls with weights == NULL and change them with kt_plan_set_weights.  A recorded first_step != 0 would reset the
- *    momentum on every replay, so kt_bucket_unpack_sgd refuses it under
- *    capture (KT_EUNSUPPORTED).
+ *    kernel node's parameters.  Or keep them out of the recording: record
+ *    kt_weighted_reduce / kt_fused_step with weights == NULL and change the
+ *    weights with kt_plan_set_weights; record kt_bucket_unpack_sgd_resident
+ *    and change scale, lr, momentum and weight_decay with kt_plan_set_sgd.
+ *    A recorded first_step != 0 would reset the momentum on every replay, so
+ *    the SGD calls refuse it under capture (KT_EUNSUPPORTED).
  *  - Streams passed to device calls should outlive the plan.  If the stream of
  *    an earlier call has been destroyed, the library waits for the whole
  *    device instead of that stream when it recycles a pointer table.
@@ -376,6 +378,32 @@ KT_API kt_status kt_bucket_unpack_sgd_master(kt_plan *plan, int bucket,
                                              void *const *model_ptrs, float lr,
                                              float momentum, float weight_decay,
                                              int first_step, void *stream);
+
+/*
+ * Device-resident optimizer scalars, for recorded graphs that must follow a
+ * learning-rate schedule (Sec. IV-B trains with a stepped learning rate).
+ * kt_plan_set_sgd copies scale, lr, momentum and weight_decay into device
+ * memory owned by the plan, on `stream`, ordered behind the work already
+ * enqueued there.  kt_bucket_unpack_sgd_resident is kt_bucket_unpack_sgd
+ * (model_ptrs == NULL) or kt_bucket_unpack_sgd_master (model_ptrs != NULL)
+ * with these four values read from device memory when the kernel runs; the
+ * arithmetic is the same, and a graph recorded with it applies, on every
+ * replay, whatever the last kt_plan_set_sgd on the replaying stream (or one
+ * synchronised with it) has written.
+ *
+ * Errors: kt_plan_set_sgd: KT_EINVAL (NULL plan), KT_EUNSUPPORTED under stream
+ * capture (the copy cannot be recorded).  kt_bucket_unpack_sgd_resident: as
+ * kt_bucket_unpack_sgd[_master], and KT_EINVAL if no scalars were set.
+ */
+KT_API kt_status kt_plan_set_sgd(kt_plan *plan, float scale, float lr,
+                                 float momentum, float weight_decay,
+                                 void *stream);
+KT_API kt_status kt_bucket_unpack_sgd_resident(kt_plan *plan, int bucket,
+                                               const void *const *bucket_bufs,
+                                               void *const *param_ptrs,
+                                               void *const *momentum_ptrs,
+                                               void *const *model_ptrs,
+                                               int first_step, void *stream);
 
 /*
  * kt_fused_step for callers that cannot allocate device memory: code that runs

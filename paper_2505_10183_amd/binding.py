@@ -77,6 +77,11 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd_master.restype = i32
         L.kt_plan_set_weights.argtypes = [vp, c.POINTER(c.c_float), i32, vp]
         L.kt_plan_set_weights.restype = i32
+        L.kt_plan_set_sgd.argtypes = [vp, c.c_float, c.c_float, c.c_float, c.c_float, vp]
+        L.kt_plan_set_sgd.restype = i32
+        L.kt_bucket_unpack_sgd_resident.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), c.POINTER(vp), c.POINTER(vp),
+                                                    i32, vp]
+        L.kt_bucket_unpack_sgd_resident.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -321,3 +326,19 @@ class Plan:
                                                  self._arr(models, T, "tensor_ptrs (model parameters)"), float(lr),
                                                  float(momentum), float(weight_decay), int(bool(first_step)),
                                                  _stream(stream)))
+
+    def kt_plan_set_sgd(self, scale: float, lr: float, momentum: float, weight_decay: float, stream=None):
+        """Copy the optimizer scalars into the plan's device memory (read by kt_bucket_unpack_sgd_resident)."""
+        _check(lib().kt_plan_set_sgd(self._h, float(scale), float(lr), float(momentum), float(weight_decay),
+                                     _stream(stream)))
+
+    def kt_bucket_unpack_sgd_resident(self, bucket: int, bucket_bufs, params, momenta, models, first_step: bool,
+                                      stream=None):
+        """SGD on unpack with scale, lr, momentum and weight decay as set by kt_plan_set_sgd; models=None: no
+        bf16 model copy."""
+        T, nb = len(self.numels), self.num_buckets
+        m = None if models is None else self._arr(models, T, "tensor_ptrs (model parameters)")
+        _check(lib().kt_bucket_unpack_sgd_resident(self._h, bucket, self._arr(bucket_bufs, nb, "bucket_bufs"),
+                                                   self._arr(params, T, "tensor_ptrs (parameters)"),
+                                                   self._arr(momenta, T, "tensor_ptrs (momentum)"), m,
+                                                   int(bool(first_step)), _stream(stream)))

@@ -127,6 +127,9 @@ struct kt_plan {
     // device, a small ring of pinned staging copies so that successive updates do not wait
     float *dev_w = nullptr;
     int dev_w_K = 0;
+    // device-resident optimizer scalars (kt_plan_set_sgd): {scale, lr, momentum, weight decay},
+    // uploaded through the same staging ring
+    float *dev_sgd = nullptr;
     float *w_stage = nullptr;                 // KT_WSTAGE * KT_MAX_PEERS floats, pinned
     hipEvent_t w_done[4] = {nullptr, nullptr, nullptr, nullptr};
     int w_head = 0;
@@ -178,6 +181,7 @@ extern "C" kt_status kt_plan_destroy(kt_plan *p)
         for (Tick &t : p->ticks)
             if (t.ev) (void)hipEventDestroy(t.ev);
         if (p->dev_w) (void)hipFree(p->dev_w);
+        if (p->dev_sgd) (void)hipFree(p->dev_sgd);
         if (p->w_stage) (void)hipHostFree(p->w_stage);
         for (hipEvent_t ev : p->w_done)
             if (ev) (void)hipEventDestroy(ev);
@@ -571,6 +575,45 @@ extern "C" kt_status kt_weighted_reduce(kt_plan *p, int bucket, const void *cons
     KT_GUARD_END("kt_weighted_reduce")
 }
 
+// Copies n (<= KT_MAX_PEERS) floats into a small device array of the plan (allocated on first
+// use, KT_MAX_PEERS floats, the rest zero) in stream order, through a ring of pinned staging
+// copies so that successive updates do not wait for each other.  Not under stream capture.
+static kt_status push_resident(kt_plan *p, float **dev, const float *src, int n, hipStream_t s)
+{
+    kt_status st = ensure_device(p, s);
+    if (st != KT_OK) return st;
+    hipError_t e;
+    if (!p->w_stage) {
+        void *h = nullptr;
+        e = hipHostMalloc(&h, KT_WSTAGE * KT_MAX_PEERS * sizeof(float), hipHostMallocDefault);
+        if (e != hipSuccess) return hip_fail("hipHostMalloc(resident scalars)", e);
+        p->w_stage = static_cast<float *>(h);
+    }
+    if (!*dev) {
+        void *d = nullptr;
+        e = hipMalloc(&d, KT_MAX_PEERS * sizeof(float));
+        if (e != hipSuccess) return hip_fail("hipMalloc(resident scalars)", e);
+        *dev = static_cast<float *>(d);
+    }
+    const int i = p->w_head;
+    p->w_head = (i + 1) % KT_WSTAGE;
+    if (!p->w_done[i]) {
+        e = hipEventCreateWithFlags(&p->w_done[i], hipEventDisableTiming);
+        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
+    } else {
+        e = hipEventSynchronize(p->w_done[i]);        // the upload that last used this staging copy
+        if (e != hipSuccess) return hip_fail("hipEventSynchronize", e);
+    }
+    float *stage = p->w_stage + (size_t)i * KT_MAX_PEERS;
+    memset(stage, 0, KT_MAX_PEERS * sizeof(float));
+    memcpy(stage, src, (size_t)n * sizeof(float));
+    e = hipMemcpyAsync(*dev, stage, KT_MAX_PEERS * sizeof(float), hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_fail("hipMemcpyAsync(resident scalars)", e);
+    e = hipEventRecord(p->w_done[i], s);
+    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
+    return KT_OK;
+}
+
 extern "C" kt_status kt_plan_set_weights(kt_plan *p, const float *weights, int K, void *stream)
 {
     KT_GUARD_BEGIN
@@ -585,37 +628,29 @@ extern "C" kt_status kt_plan_set_weights(kt_plan *p, const float *weights, int K
                      "that replays the graph", who);
         return KT_EUNSUPPORTED;
     }
-    kt_status st = ensure_device(p, s);
+    kt_status st = push_resident(p, &p->dev_w, weights, K, s);
     if (st != KT_OK) return st;
-    hipError_t e;
-    if (!p->dev_w) {
-        void *d = nullptr, *h = nullptr;
-        e = hipMalloc(&d, KT_MAX_PEERS * sizeof(float));
-        if (e != hipSuccess) return hip_fail("hipMalloc(weights)", e);
-        e = hipHostMalloc(&h, KT_WSTAGE * KT_MAX_PEERS * sizeof(float), hipHostMallocDefault);
-        if (e != hipSuccess) { (void)hipFree(d); return hip_fail("hipHostMalloc(weights)", e); }
-        p->dev_w = static_cast<float *>(d);
-        p->w_stage = static_cast<float *>(h);
-    }
-    const int i = p->w_head;
-    p->w_head = (i + 1) % KT_WSTAGE;
-    if (!p->w_done[i]) {
-        e = hipEventCreateWithFlags(&p->w_done[i], hipEventDisableTiming);
-        if (e != hipSuccess) return hip_fail("hipEventCreate", e);
-    } else {
-        e = hipEventSynchronize(p->w_done[i]);        // the upload that last used this staging copy
-        if (e != hipSuccess) return hip_fail("hipEventSynchronize", e);
-    }
-    float *stage = p->w_stage + (size_t)i * KT_MAX_PEERS;
-    memset(stage, 0, KT_MAX_PEERS * sizeof(float));
-    memcpy(stage, weights, (size_t)K * sizeof(float));
-    e = hipMemcpyAsync(p->dev_w, stage, KT_MAX_PEERS * sizeof(float), hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return hip_fail("hipMemcpyAsync(weights)", e);
-    e = hipEventRecord(p->w_done[i], s);
-    if (e != hipSuccess) return hip_fail("hipEventRecord", e);
     p->dev_w_K = K;
     return KT_OK;
     KT_GUARD_END("kt_plan_set_weights")
+}
+
+extern "C" kt_status kt_plan_set_sgd(kt_plan *p, float scale, float lr, float momentum, float weight_decay,
+                                     void *stream)
+{
+    KT_GUARD_BEGIN
+    const char *who = "kt_plan_set_sgd";
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (capturing(s)) {
+        kt_set_error("%s: the upload cannot be recorded into a graph; call it outside stream capture, on the stream "
+                     "that replays the graph", who);
+        return KT_EUNSUPPORTED;
+    }
+    const float v[4] = {scale, lr, momentum, weight_decay};
+    return push_resident(p, &p->dev_sgd, v, 4, s);
+    KT_GUARD_END("kt_plan_set_sgd")
 }
 
 kt_status kt_fused_prepare(const kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
@@ -703,7 +738,7 @@ extern "C" kt_status kt_fused_step(kt_plan *p, int bucket, const void *const *lo
 static kt_status unpack_sgd_impl(kt_plan *p, int bucket, const void *const *bucket_bufs, float scale,
                                  void *const *param_ptrs, void *const *momentum_ptrs, void *const *model_ptrs,
                                  bool master, float lr, float momentum, float weight_decay, int first_step,
-                                 void *stream, const char *who)
+                                 void *stream, const char *who, bool resident = false)
 {
     KT_GUARD_BEGIN
     if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
@@ -714,6 +749,7 @@ static kt_status unpack_sgd_impl(kt_plan *p, int bucket, const void *const *buck
     kt_status st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
     if (st != KT_OK || ntiles == 0) return st;
     if (!bucket_bufs || !param_ptrs || !momentum_ptrs || (master && !model_ptrs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    if (resident && !p->dev_sgd) { kt_set_error("%s: no optimizer scalars set with kt_plan_set_sgd", who); return KT_EINVAL; }
     if (first_step && capturing(s)) {
         kt_set_error("%s: first_step is frozen into a recorded kernel and would reset the momentum on every replay; "
                      "make the first step outside stream capture", who);
@@ -761,7 +797,7 @@ static kt_status unpack_sgd_impl(kt_plan *p, int bucket, const void *const *buck
     st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
     if (st != KT_OK) return st;
     uint64_t *d = static_cast<uint64_t *>(slot->dev);
-    KtSgd a{scale, lr, momentum, weight_decay, first_step ? 1 : 0};
+    KtSgd a{scale, lr, momentum, weight_decay, first_step ? 1 : 0, resident ? p->dev_sgd : nullptr};
     int e = kt_launch_unpack_sgd(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d + 2 * T + M),
                                  reinterpret_cast<void *const *>(d), reinterpret_cast<void *const *>(d + T),
                                  master ? reinterpret_cast<void *const *>(d + 2 * T) : nullptr, a, vec, stream);
@@ -785,4 +821,12 @@ extern "C" kt_status kt_bucket_unpack_sgd_master(kt_plan *p, int bucket, const v
 {
     return unpack_sgd_impl(p, bucket, bucket_bufs, scale, master_ptrs, momentum_ptrs, model_ptrs, true, lr, momentum,
                            weight_decay, first_step, stream, "kt_bucket_unpack_sgd_master");
+}
+
+extern "C" kt_status kt_bucket_unpack_sgd_resident(kt_plan *p, int bucket, const void *const *bucket_bufs,
+                                                   void *const *param_ptrs, void *const *momentum_ptrs,
+                                                   void *const *model_ptrs, int first_step, void *stream)
+{
+    return unpack_sgd_impl(p, bucket, bucket_bufs, 0.0f, param_ptrs, momentum_ptrs, model_ptrs, model_ptrs != nullptr,
+                           0.0f, 0.0f, 0.0f, first_step, stream, "kt_bucket_unpack_sgd_resident", true);
 }

@@ -89,6 +89,7 @@ int kt_launch_fused(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
 struct KtSgd {
     float scale, lr, mu, wd;
     int first;
+    const float *dev;   // non-NULL: {scale, lr, mu, wd} are read from these 4 device floats when the kernel runs
 };
 int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                          int64_t ntiles, const void *const *d_bucket_ptrs,

@@ -12,7 +12,46 @@
 #define KT_REDUCE_OCC
 #endif
 
+// Design-choice knobs of the main kernel (defaults are what measured best; the others are kept
+// so that the comparison can be repeated).
+//   KT_REDUCE_LAYOUT  0: vector u of lane t is u*256 + t (a workgroup's load covers 4 KiB)
+//                     1: each wavefront owns 4 KiB of the tile (vector wave*256 + u*64 + lane)
+//   KT_REDUCE_ISSUE   0: loads issued vector by vector, the K peers of a vector together
+//                     1: peer by peer, the 4 vectors of a peer together
+//   KT_REDUCE_XCD     0: tile = blockIdx.x (neighbouring tiles on different XCDs)
+//                     1: each of the 8 XCDs walks its own contiguous eighth of the tiles
+#ifndef KT_REDUCE_LAYOUT
+#define KT_REDUCE_LAYOUT 0
+#endif
+#ifndef KT_REDUCE_ISSUE
+#define KT_REDUCE_ISSUE 0
+#endif
+#ifndef KT_REDUCE_XCD
+#define KT_REDUCE_XCD 0
+#endif
+
 namespace {
+
+__device__ __forceinline__ int64_t reduce_tile_index()
+{
+#if KT_REDUCE_XCD
+    // workgroups are dealt round-robin to the XCDs: blockIdx.x % 8 names the XCD
+    const uint32_t x = blockIdx.x & 7u, i = blockIdx.x >> 3, q = gridDim.x >> 3, r = gridDim.x & 7u;
+    return (int64_t)x * q + (x < r ? x : r) + i;
+#else
+    return blockIdx.x;
+#endif
+}
+
+__device__ __forceinline__ int reduce_vec_index(int u, int tid)
+{
+#if KT_REDUCE_LAYOUT == 1
+    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    return (tid >> 6) * (VPT * 64) + u * 64 + (tid & 63);
+#else
+    return u * KT_BLOCK + tid;
+#endif
+}
 
 template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
@@ -23,7 +62,7 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
     constexpr int VPT = KT_TILE_VECS / KT_BLOCK;   // vectors per lane, K loads each, all in flight at once
 
-    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const KtTile tl = tb.tiles[tile0 + reduce_tile_index()];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const int tid = threadIdx.x;
 
@@ -40,18 +79,26 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
 
     if (nvec == KT_TILE_VECS) {
         u32x4 r[VPT][K];
+#if KT_REDUCE_ISSUE == 1
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + reduce_vec_index(u, tid));
+#else
 #pragma unroll
         for (int u = 0; u < VPT; ++u)
 #pragma unroll
             for (int k = 0; k < K; ++k)
-                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + u * KT_BLOCK + tid);
+                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + reduce_vec_index(u, tid));
+#endif
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             Acc<T> acc;
             acc.first(r[u][0], w[0]);
 #pragma unroll
             for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
-            st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc.finish());
+            st_vec(reinterpret_cast<u32x4 *>(out) + reduce_vec_index(u, tid), acc.finish());
         }
     } else {
         for (int v = tid; v < nvec; v += KT_BLOCK) {

@@ -208,12 +208,23 @@ __device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x
     }
 }
 
-template <typename T, bool MASTER>
+// DEVS: the four optimizer scalars come from device memory (uniform scalar loads, issued with
+// the tile-table load) instead of the kernel-argument block, so that a recorded launch follows
+// a learning-rate schedule.  A separate instantiation: launches with scalars by value run the
+// code they always ran.
+template <typename T, bool MASTER, bool DEVS>
 __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables tb, int64_t tile0,
                                                                  const void *const *bucket_ptrs,
                                                                  void *const *param_ptrs, void *const *mom_ptrs,
                                                                  void *const *model_ptrs, KtSgd a, int vec_ok)
 {
+    if (DEVS) {
+        const float *d = a.dev;
+        a.scale = d[0];
+        a.lr = d[1];
+        a.mu = d[2];
+        a.wd = d[3];
+    }
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
     constexpr int QPT = SgdShape<T>::QPT, SPLIT = SgdShape<T>::SPLIT;
@@ -287,8 +298,15 @@ int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0, i
         const int64_t now = ntiles - done < per_launch ? ntiles - done : per_launch;
         const dim3 grid((unsigned)(now * split));
         const int64_t t0 = tile0 + done;
-#define KT_SGD_LAUNCH(TT, MM) \
-    kt_unpack_sgd_kernel<TT, MM><<<grid, block, 0, s>>>(tb, t0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, d_model_ptrs, a, v)
+#define KT_SGD_LAUNCH(TT, MM)                                                                                        \
+    do {                                                                                                            \
+        if (a.dev)                                                                                                  \
+            kt_unpack_sgd_kernel<TT, MM, true><<<grid, block, 0, s>>>(tb, t0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, \
+                                                                      d_model_ptrs, a, v);                         \
+        else                                                                                                        \
+            kt_unpack_sgd_kernel<TT, MM, false><<<grid, block, 0, s>>>(tb, t0, d_bucket_ptrs, d_param_ptrs, d_mom_ptrs, \
+                                                                       d_model_ptrs, a, v);                        \
+    } while (0)
         if (dt == KT_F32) {
             if (d_model_ptrs) KT_SGD_LAUNCH(float, true); else KT_SGD_LAUNCH(float, false);
         } else {

@@ -309,3 +309,87 @@ def test_recorded_step_follows_resident_weights():
         g2.capture_end()
     assert err is not None and err.status_name == "KT_EUNSUPPORTED"
 
+
+
+@pytest.mark.parametrize("dtype,master", [("f32", False), ("bf16", True)])
+def test_recorded_sgd_step_follows_resident_scalars(dtype, master):
+    """kt_bucket_unpack_sgd_resident reads scale, lr, momentum and weight decay
+    from the plan's device memory when it runs: one recording follows a stepped
+    learning rate (and a changed scale) pushed with kt_plan_set_sgd.  Eager
+    calls equal the by-value entry points bit for bit."""
+    K = 3
+    w = wl.ragged_workload(dtype=dtype, K=K, seed=79, n_tensors=30)
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+    L = oracle.assign_buckets(w.numels, w.elem_size, w.bucket_cap_bytes, 16)
+    bufs = [wl.flat_normal(n, dtype, 1e-2, 900 + b, DEV) for b, n in enumerate(plan.bucket_elems())]
+    hb = [host(b) for b in bufs]
+    T = len(w.numels)
+    gen = torch.Generator(DEV).manual_seed(5)
+    params = [torch.randn(n, generator=gen, device=DEV) for n in w.numels]
+    moms = [torch.full((n,), float("nan"), device=DEV) for n in w.numels]
+    models = [torch.zeros(n, dtype=torch.bfloat16, device=DEV) for n in w.numels] if master else None
+    hp, hv = [host(p) for p in params], [host(v) for v in moms]
+    hm = None
+
+    def advance(scale, lr, first):
+        nonlocal hp, hv, hm
+        if master:
+            hp, hv, hm = oracle.unpack_sgd_master(L, hb, w.numels, scale, hp, hv, lr, 0.9, 5e-4, first, dtype, "S")
+        else:
+            hp, hv = oracle.unpack_sgd(L, hb, w.numels, scale, hp, hv, lr, 0.9, 5e-4, first, dtype, "S")
+
+    def check(tag):
+        torch.cuda.synchronize()
+        for t in range(T):
+            assert raw(host(params[t])).tobytes() == raw(hp[t]).tobytes(), (tag, "p", t)
+            assert raw(host(moms[t])).tobytes() == raw(hv[t]).tobytes(), (tag, "v", t)
+            if master:
+                assert host(models[t]).tobytes() == hm[t].tobytes(), (tag, "model", t)
+
+    with pytest.raises(kt.KtError):
+        plan.kt_bucket_unpack_sgd_resident(-1, bufs, params, moms, models, True)     # nothing set yet
+    plan.kt_plan_set_sgd(1.0, 0.1, 0.9, 5e-4)
+    plan.kt_bucket_unpack_sgd_resident(-1, bufs, params, moms, models, True)         # first step, eager
+    advance(1.0, 0.1, True)
+    check("first step")
+    # same state through the by-value entry: bit-identical
+    p2, v2 = [t.clone() for t in params], [t.clone() for t in moms]
+    m2 = [torch.zeros_like(t) for t in models] if master else None
+    plan.kt_bucket_unpack_sgd_resident(-1, bufs, params, moms, models, False)
+    if master:
+        plan.kt_bucket_unpack_sgd_master(-1, bufs, 1.0, p2, v2, m2, 0.1, 0.9, 5e-4, False)
+    else:
+        plan.kt_bucket_unpack_sgd(-1, bufs, 1.0, p2, v2, 0.1, 0.9, 5e-4, False)
+    advance(1.0, 0.1, False)
+    check("second step")
+    for t in range(T):
+        assert torch.equal(params[t], p2[t]) and torch.equal(moms[t], v2[t])
+        if master:
+            assert torch.equal(models[t], m2[t])
+    # a first step cannot be recorded; later steps can
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    err = None
+    with torch.cuda.stream(s):
+        g.capture_begin()
+        try:
+            plan.kt_bucket_unpack_sgd_resident(-1, bufs, params, moms, models, True)
+        except kt.KtError as e:
+            err = e
+        try:
+            plan.kt_plan_set_sgd(1.0, 0.1, 0.9, 5e-4, stream=s)
+        except kt.KtError as e:
+            err2 = e
+        plan.kt_bucket_unpack_sgd_resident(-1, bufs, params, moms, models, False, stream=s)
+        g.capture_end()
+    assert err is not None and err.status_name == "KT_EUNSUPPORTED"
+    assert err2.status_name == "KT_EUNSUPPORTED"
+    torch.cuda.synchronize()
+    check("after capture")                       # recording ran nothing
+    # a stepped learning rate, and a changed scale, with eager work and a sync between replays
+    for r, (scale, lr) in enumerate([(1.0, 0.1), (1.0, 0.01), (0.5, 0.01), (0.37, 0.001), (0.37, 0.001)]):
+        plan.kt_plan_set_sgd(scale, lr, 0.9, 5e-4)
+        torch.cuda.synchronize()
+        g.replay()
+        advance(scale, lr, False)
+        check("replay %d" % r)

@@ -352,6 +352,27 @@ def test_resident_weights_argument_errors_without_gpu():
     assert ei.value.status_name == "KT_EINVAL"
 
 
+def test_resident_sgd_scalars_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "f32", 0, 16)
+    L = kt.binding.lib()
+    assert L.kt_plan_set_sgd(None, 1.0, 0.1, 0.9, 0.0, None) == 1
+    ok_p, ok_v, ok_m, ok_b = [16000, 32000], [48000, 64000], [80000, 96000], [4096]
+    # no scalars set yet: refused before anything touches the GPU, with or without the model copy
+    for models in (None, ok_m):
+        with pytest.raises(kt.KtError) as ei:
+            p.kt_bucket_unpack_sgd_resident(-1, ok_b, ok_p, ok_v, models, False, stream=0)
+        assert ei.value.status_name == "KT_EINVAL" and "kt_plan_set_sgd" in str(ei.value)
+    # the pointer checks of the by-value calls apply
+    with pytest.raises(kt.KtError) as ei:
+        p.kt_bucket_unpack_sgd_resident(3, ok_b, ok_p, ok_v, None, False, stream=0)
+    assert ei.value.status_name == "KT_EINVAL"
+    with pytest.raises(kt.KtError) as ei:
+        p.kt_bucket_unpack_sgd_resident(-1, ok_b, [0, 32000], ok_v, None, False, stream=0)
+    assert ei.value.status_name == "KT_EINVAL"
+    with pytest.raises(ValueError):
+        p.kt_bucket_unpack_sgd_resident(-1, ok_b, ok_p, ok_v, ok_m[:1], False, stream=0)
+
+
 def test_unpack_sgd_master_argument_errors_without_gpu():
     p = kt.Plan([10, 20], "bf16", 0, 16)
     ok_p, ok_v, ok_m, ok_b = [16000, 32000], [48000, 64000], [80000, 96000], [4096]
