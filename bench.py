@@ -30,7 +30,8 @@ HBM_PEAK_GBS = 8000.0
 # summarised under profiles/ (reads scaled by the factor the 1 GiB calibration copy gives).
 # They describe the kernel sources with the digest below; after any change to those
 # sources the figure is reported as null until the counters are taken again.
-KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip", "kt_sgd.hip")
+KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_sgd_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip",
+                  "kt_sgd.hip", "kt_fused_sgd.hip")
 TRAFFIC_SOURCES_SHA = "311403823b51f89a"
 TRAFFIC_BYTES = {"decoder_1p3b": 23704862575, "vit_b16": 3119145150}
 
@@ -166,6 +167,11 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
     a_m = p.marshal(models)
     ms_sgd_master = loop(lambda: p.kt_bucket_unpack_sgd_master(-1, st["a_outs"], 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4,
                                                                False))
+    # K gradient copies -> updated parameters in one pass: K*s + 16 bytes per element (+ 2 with the model copy)
+    ms_fsgd = loop(lambda: p.kt_fused_step_sgd(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0, a_p, a_v, None,
+                                               0.1, 0.9, 5e-4, False))
+    ms_fsgd_master = loop(lambda: p.kt_fused_step_sgd(-1, st["a_local"], st["a_others"], st["K"], st["a_w"], 1.0, a_p, a_v,
+                                                      a_m, 0.1, 0.9, 5e-4, False))
     del params, moms, models
     # the chained step recorded once into a HIP graph and replayed (launch-bound small sets);
     # optional context: a failure here must not take the headline measurement down
@@ -204,6 +210,9 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
         "fused_inplace_ms": ms_fused_inplace, "fused_inplace_GBps": (K + 1) * s * e / (ms_fused_inplace * 1e-3) / 1e9,
         "unpack_sgd_ms": ms_sgd, "unpack_sgd_GBps": (s + 16) * e / (ms_sgd * 1e-3) / 1e9,
         "unpack_sgd_master_ms": ms_sgd_master, "unpack_sgd_master_GBps": (s + 18) * e / (ms_sgd_master * 1e-3) / 1e9,
+        "fused_sgd_ms": ms_fsgd, "fused_sgd_GBps": (K * s + 16) * e / (ms_fsgd * 1e-3) / 1e9,
+        "fused_sgd_buckets_per_s": st["nb"] / (ms_fsgd * 1e-3),
+        "fused_sgd_master_ms": ms_fsgd_master, "fused_sgd_master_GBps": (K * s + 18) * e / (ms_fsgd_master * 1e-3) / 1e9,
     }
     if ms_graph:
         res.update({"graph_step_ms": ms_graph, "graph_step_GBps": (K + 5) * s * e / (ms_graph * 1e-3) / 1e9,
@@ -452,6 +461,54 @@ def ceilings(dev, reps=10):
     return res
 
 
+def k_sweep(dev, reps=10, passes=2):
+    """Flat 1 GiB fp32 buffers, K = 1..8 peers: the read-only probe on K buffers, kt_weighted_reduce of
+    K buffers into another, and in place over the first.  Prints one line per K and pass: GB/s of
+    (K reads [+ 1 write]) x 1 GiB and the times, from which the cost of the written gigabyte on
+    top of the reads follows."""
+    import ctypes
+    import torch
+    import paper_2505_10183_amd as kt
+    n = 1 << 28
+    bufs = [torch.empty(n, dtype=torch.float32, device=dev).normal_() for _ in range(8)]
+    out = torch.empty(n, dtype=torch.float32, device=dev)
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    plan = kt.Plan([n], "f32", 0, 16)
+    probe = load_probe()
+    if probe is None:
+        raise RuntimeError("libkt_bench_probe.so is not built")
+    stream = torch.cuda.current_stream().cuda_stream
+    gib = float(n * 4)
+
+    def loop(fn):
+        for _ in range(3):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e-3
+
+    ao, a0 = plan.marshal([out]), plan.marshal(bufs[:1])
+    print("# flat 1 GiB fp32 buffers; GB/s of (K reads [+ 1 write]) x 1 GiB; %d launches after 3 warm-up" % reps)
+    print("# K  read_only  reduce_out_of_place  reduce_in_place  |  ms: read_only  out_of_place  in_place")
+    for _ in range(passes):
+        for K in (1, 2, 3, 4, 6, 8):
+            ak = plan.marshal(bufs[:K])
+            w = (ctypes.c_float * K)(*([1.0 / K] * K))
+            tr = loop(lambda: probe.bench_probe_read(ak, K, int(gib), sink.data_ptr(), stream))
+            to = loop(lambda: plan.kt_weighted_reduce(-1, ak, K, w, ao))
+            ti = loop(lambda: plan.kt_weighted_reduce(-1, ak, K, w, a0))
+            print("  %d  %9.1f  %19.1f  %15.1f  |  %13.4f  %12.4f  %8.4f"
+                  % (K, K * gib / tr / 1e9, (K + 1) * gib / to / 1e9, (K + 1) * gib / ti / 1e9, tr * 1e3, to * 1e3, ti * 1e3))
+            sys.stdout.flush()
+    assert float(sink.abs().sum()) == 0.0
+    plan.close()
+
+
 def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
     """Interleaved comparison of library builds (paper_2505_10183_amd/build.py --out ... -D...)
     in ONE process on ONE set of device buffers: every round times every kernel on every
@@ -527,6 +584,12 @@ def ab_compare(workload, kernel_names, variants, dev, rounds=5, reps=10):
             "sgd": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_p, a_v, 0.1, 0.9, 5e-4, False), s + 16),
             "sgd_master": (lambda: p.kt_bucket_unpack_sgd_master(-1, a_o, 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4, False), s + 18),
             "sgd_views": (lambda: p.kt_bucket_unpack_sgd(-1, a_o, 1.0, a_vp, a_vv, 0.1, 0.9, 5e-4, False), s + 16),
+            "fused_sgd": (lambda: p.kt_fused_step_sgd(-1, a_l, a_ot, K, a_w, 1.0, a_p, a_v, None, 0.1, 0.9, 5e-4, False),
+                          K * s + 16),
+            "fused_sgd_master": (lambda: p.kt_fused_step_sgd(-1, a_l, a_ot, K, a_w, 1.0, a_p, a_v, a_m, 0.1, 0.9, 5e-4,
+                                                             False), K * s + 18),
+            "fused_sgd_views": (lambda: p.kt_fused_step_sgd(-1, a_vl, a_ot, K, a_w, 1.0, a_vp, a_vv, None, 0.1, 0.9, 5e-4,
+                                                            False), K * s + 16),
             "sgd_resident_scalars": (lambda: p.kt_bucket_unpack_sgd_resident(-1, a_o, a_p, a_v, None, False), s + 16),
         }
 
@@ -594,6 +657,8 @@ def main():
     ap.add_argument("--ceilings-only", action="store_true",
                     help="run only the memory-system probes on flat 1 GiB buffers and print their JSON "
                          "(the command the counter summaries under profiles/ are taken with)")
+    ap.add_argument("--k-sweep", action="store_true",
+                    help="read-only probe and reduce on flat 1 GiB buffers for K = 1..8; prints a table")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run a plain 1 GiB device copy (torch copy_) three times, so that a counter "
                          "trace of this command holds a kernel of known traffic to scale FETCH_SIZE/WRITE_SIZE by")
@@ -630,6 +695,9 @@ def main():
 
     if args.ceilings_only:
         print(json.dumps({"memory_system": ceilings(dev)}))
+        return
+    if args.k_sweep:
+        k_sweep(dev)
         return
     res, st = time_workload(args.workload, args.steps, args.warmup, dev, not args.out_of_place, args.misalign)
     w = st["w"]

@@ -44,7 +44,8 @@
  *    kernel node's parameters.  Or keep them out of the recording: record
  *    kt_weighted_reduce / kt_fused_step with weights == NULL and change the
  *    weights with kt_plan_set_weights; record kt_bucket_unpack_sgd_resident
- *    and change scale, lr, momentum and weight_decay with kt_plan_set_sgd.
+ *    (or kt_fused_step_sgd_resident) and change scale, lr, momentum and
+ *    weight_decay with kt_plan_set_sgd.
  *    A recorded first_step != 0 would reset the momentum on every replay, so
  *    the SGD calls refuse it under capture (KT_EUNSUPPORTED).
  *  - Streams passed to device calls should outlive the plan.  If the stream of
@@ -404,6 +405,55 @@ KT_API kt_status kt_bucket_unpack_sgd_resident(kt_plan *plan, int bucket,
                                                void *const *momentum_ptrs,
                                                void *const *model_ptrs,
                                                int first_step, void *stream);
+
+/*
+ * The single pass from K gradient copies to updated parameters: kt_fused_step
+ * and kt_bucket_unpack_sgd[_master] in one kernel.  Per element of every
+ * tensor of the selected bucket(s)
+ *     r  = round(w_0 * local_t[i] + sum_{k=1}^{K-1} w_k * peer_{b,k}[off_t + i])
+ * with the arithmetic and rounding of kt_weighted_reduce (r in the bucket's
+ * element type), then the update of kt_bucket_unpack_sgd on g = scale * r
+ * (Sec. IV-B's optimizer).  The results are bit-identical to kt_bucket_pack ->
+ * kt_weighted_reduce -> kt_bucket_unpack_sgd[_master]; the reduced gradient is
+ * never written, so (K-1)*s + s + 16 bytes per element move instead of
+ * (K+1)*s + s + 16 for kt_fused_step followed by an optimizer pass.
+ *
+ *   local_tensor_ptrs host, in: T device pointers, this device's gradients
+ *                               (peer 0), read only.
+ *   peer_bufs         host, in: device pointers, entry [b * (K-1) + (k-1)] =
+ *                               peer k's copy of bucket b, k = 1..K-1
+ *                               (ignored when K == 1).
+ *   weights           host, in: K weights, or NULL for the weights set with
+ *                               kt_plan_set_weights.
+ *   param_ptrs, momentum_ptrs host, in: T device pointers each, binary32,
+ *                               updated in place (momentum is written without
+ *                               being read when first_step != 0).
+ *   model_ptrs        host, in: NULL, or T device pointers to bf16 tensors that
+ *                               receive every updated parameter rounded to
+ *                               nearest-even (mixed precision).
+ * Gradients, parameters, momentum, model parameters and peer buckets must not
+ * overlap.  16-byte aligned addresses (8 for the model copy) take the vector
+ * path.  kt_fused_step_sgd_resident reads the weights (kt_plan_set_weights) and
+ * scale, lr, momentum, weight_decay (kt_plan_set_sgd) from the plan's device
+ * memory when the kernel runs, for recorded graphs; KT_EINVAL if either was not
+ * set.  A first step is refused under stream capture (KT_EUNSUPPORTED).
+ */
+KT_API kt_status kt_fused_step_sgd(kt_plan *plan, int bucket,
+                                   const void *const *local_tensor_ptrs,
+                                   const void *const *peer_bufs, int K,
+                                   const float *weights, float scale,
+                                   void *const *param_ptrs,
+                                   void *const *momentum_ptrs,
+                                   void *const *model_ptrs, float lr,
+                                   float momentum, float weight_decay,
+                                   int first_step, void *stream);
+KT_API kt_status kt_fused_step_sgd_resident(kt_plan *plan, int bucket,
+                                            const void *const *local_tensor_ptrs,
+                                            const void *const *peer_bufs, int K,
+                                            void *const *param_ptrs,
+                                            void *const *momentum_ptrs,
+                                            void *const *model_ptrs,
+                                            int first_step, void *stream);
 
 /*
  * kt_fused_step for callers that cannot allocate device memory: code that runs

@@ -82,6 +82,13 @@ def lib() -> ctypes.CDLL:
         L.kt_bucket_unpack_sgd_resident.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), c.POINTER(vp), c.POINTER(vp),
                                                     i32, vp]
         L.kt_bucket_unpack_sgd_resident.restype = i32
+        L.kt_fused_step_sgd.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
+                                        c.POINTER(vp), c.POINTER(vp), c.POINTER(vp), c.c_float, c.c_float, c.c_float,
+                                        i32, vp]
+        L.kt_fused_step_sgd.restype = i32
+        L.kt_fused_step_sgd_resident.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(vp), c.POINTER(vp),
+                                                 c.POINTER(vp), i32, vp]
+        L.kt_fused_step_sgd_resident.restype = i32
         L.kt_fused_step.argtypes = [vp, i32, c.POINTER(vp), c.POINTER(vp), i32, c.POINTER(c.c_float), c.c_float,
                                     c.POINTER(vp), vp]
         L.kt_fused_step.restype = i32
@@ -326,6 +333,35 @@ class Plan:
                                                  self._arr(models, T, "tensor_ptrs (model parameters)"), float(lr),
                                                  float(momentum), float(weight_decay), int(bool(first_step)),
                                                  _stream(stream)))
+
+    def kt_fused_step_sgd(self, bucket: int, local_tensors, peer_bufs, K: int, weights, scale: float, params, momenta,
+                          models, lr: float, momentum: float, weight_decay: float, first_step: bool, stream=None):
+        """K gradient copies -> updated parameters in one pass.  peer_bufs: flat sequence, entry
+        [b * (K-1) + (k-1)] for k = 1..K-1; models=None: no bf16 model copy."""
+        T, nb = len(self.numels), self.num_buckets
+        if not 1 <= K <= KT_MAX_PEERS:
+            _check(lib().kt_fused_step_sgd(self._h, bucket, None, None, K, None, 1.0, None, None, None, 0.0, 0.0, 0.0, 0,
+                                           _stream(stream)))
+        m = None if models is None else self._arr(models, T, "tensor_ptrs (model parameters)")
+        _check(lib().kt_fused_step_sgd(self._h, bucket, self._arr(local_tensors, T, "tensor_ptrs (local gradients)"),
+                                       self._arr(peer_bufs, nb * (K - 1), "peer_bufs"), K, self._weights(weights, K),
+                                       float(scale), self._arr(params, T, "tensor_ptrs (parameters)"),
+                                       self._arr(momenta, T, "tensor_ptrs (momentum)"), m, float(lr), float(momentum),
+                                       float(weight_decay), int(bool(first_step)), _stream(stream)))
+
+    def kt_fused_step_sgd_resident(self, bucket: int, local_tensors, peer_bufs, K: int, params, momenta, models,
+                                   first_step: bool, stream=None):
+        """kt_fused_step_sgd with the weights of kt_plan_set_weights and the scalars of kt_plan_set_sgd."""
+        T, nb = len(self.numels), self.num_buckets
+        if not 1 <= K <= KT_MAX_PEERS:
+            _check(lib().kt_fused_step_sgd_resident(self._h, bucket, None, None, K, None, None, None, 0, _stream(stream)))
+        m = None if models is None else self._arr(models, T, "tensor_ptrs (model parameters)")
+        _check(lib().kt_fused_step_sgd_resident(self._h, bucket,
+                                                self._arr(local_tensors, T, "tensor_ptrs (local gradients)"),
+                                                self._arr(peer_bufs, nb * (K - 1), "peer_bufs"), K,
+                                                self._arr(params, T, "tensor_ptrs (parameters)"),
+                                                self._arr(momenta, T, "tensor_ptrs (momentum)"), m,
+                                                int(bool(first_step)), _stream(stream)))
 
     def kt_plan_set_sgd(self, scale: float, lr: float, momentum: float, weight_decay: float, stream=None):
         """Copy the optimizer scalars into the plan's device memory (read by kt_bucket_unpack_sgd_resident)."""

@@ -25,7 +25,7 @@ def build(verbose: bool = False, extra_defines=(), out: str = LIB) -> str:
     objs = []
     tag = "" if out == LIB else ".variant%d" % os.getpid()
     for name in ("kt_plan.cpp", "kt_sampler.cpp", "kt_api.cpp", "kt_pack_unpack.hip", "kt_reduce.hip",
-                 "kt_fused.hip", "kt_sgd.hip", "kt_static.hip"):
+                 "kt_fused.hip", "kt_sgd.hip", "kt_fused_sgd.hip", "kt_static.hip"):
         src = os.path.join(CSRC, name)
         obj = os.path.join(CSRC, os.path.splitext(name)[0] + tag + ".o")
         cmd = [HIPCC] + COMMON + list(extra_defines)

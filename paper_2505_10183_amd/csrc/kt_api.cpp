@@ -830,3 +830,109 @@ extern "C" kt_status kt_bucket_unpack_sgd_resident(kt_plan *p, int bucket, const
     return unpack_sgd_impl(p, bucket, bucket_bufs, 0.0f, param_ptrs, momentum_ptrs, model_ptrs, model_ptrs != nullptr,
                            0.0f, 0.0f, 0.0f, first_step, stream, "kt_bucket_unpack_sgd_resident", true);
 }
+
+// kt_fused_step_sgd and its form with device-resident weights and optimizer scalars.
+static kt_status fused_sgd_impl(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                                const void *const *peer_bufs, int K, const float *weights, float scale,
+                                void *const *param_ptrs, void *const *momentum_ptrs, void *const *model_ptrs,
+                                float lr, float momentum, float weight_decay, int first_step, void *stream,
+                                const char *who, bool resident)
+{
+    KT_GUARD_BEGIN
+    if (!p) { kt_set_error("%s: NULL plan", who); return KT_EINVAL; }
+    std::lock_guard<std::mutex> lock(p->mu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (K < 1 || K > KT_MAX_PEERS) { kt_set_error("%s: K=%d outside [1,%d]", who, K, KT_MAX_PEERS); return KT_EINVAL; }
+    KtWeights w;
+    kt_status st = resolve_weights(p, weights, K, who, &w);
+    if (st != KT_OK) return st;
+    int b0, b1;
+    int64_t tile0, ntiles;
+    st = select(p, bucket, who, &b0, &b1, &tile0, &ntiles);
+    if (st != KT_OK || ntiles == 0) return st;
+    if (!local_tensor_ptrs || !param_ptrs || !momentum_ptrs || (K > 1 && !peer_bufs)) { kt_set_error("%s: NULL pointer array", who); return KT_EINVAL; }
+    if (resident && !p->dev_sgd) { kt_set_error("%s: no optimizer scalars set with kt_plan_set_sgd", who); return KT_EINVAL; }
+    if (first_step && capturing(s)) {
+        kt_set_error("%s: first_step is frozen into a recorded kernel and would reset the momentum on every replay; "
+                     "make the first step outside stream capture", who);
+        return KT_EUNSUPPORTED;
+    }
+    const KtHostPlan &hp = p->hp;
+    const bool master = model_ptrs != nullptr;
+    const size_t T = hp.t_numel.size(), nb = hp.b_elems.size(), KP = (size_t)(K - 1), M = master ? T : 0;
+    const uintptr_t emask = (uintptr_t)hp.elem_size - 1;
+    // table layout: [local gradients T | parameters T | momentum T | model parameters T (optional) | peers nb*(K-1)]
+    std::vector<uint64_t> &vals = call_table(3 * T + M + nb * KP);
+    for (size_t t = 0; t < T; ++t) {
+        vals[t] = reinterpret_cast<uintptr_t>(local_tensor_ptrs[t]);
+        vals[T + t] = reinterpret_cast<uintptr_t>(param_ptrs[t]);
+        vals[2 * T + t] = reinterpret_cast<uintptr_t>(momentum_ptrs[t]);
+        if (master) vals[3 * T + t] = reinterpret_cast<uintptr_t>(model_ptrs[t]);
+    }
+    const size_t P0 = 3 * T + M;
+    for (size_t i = 0; i < nb * KP; ++i) vals[P0 + i] = reinterpret_cast<uintptr_t>(peer_bufs[i]);
+    auto overlap = [](uintptr_t a, uintptr_t an, uintptr_t b, uintptr_t bn) { return an && bn && a < b + bn && b < a + an; };
+    bool vec = hp.align_bytes % KT_VEC_BYTES == 0;
+    for (int b = b0; b < b1; ++b) {
+        const uintptr_t bbytes = (uintptr_t)hp.b_elems[b] * hp.elem_size;
+        for (size_t k = 0; k < KP; ++k) {
+            const uintptr_t pp = vals[P0 + (size_t)b * KP + k];
+            if (bbytes && !pp) { kt_set_error("%s: NULL peer %zu of bucket %d", who, k + 1, b); return KT_EINVAL; }
+            if (pp & emask) { kt_set_error("%s: peer %zu of bucket %d not aligned to the element size", who, k + 1, b); return KT_EALIGN; }
+            if (pp & (KT_VEC_BYTES - 1)) vec = false;
+        }
+        for (int t = hp.b_first[b]; t < hp.b_first[b] + hp.b_count[b]; ++t) {
+            const uintptr_t lp = vals[t], pa = vals[T + t], va = vals[2 * T + t], ma = master ? vals[3 * T + t] : 0;
+            const uintptr_t ln = (uintptr_t)hp.t_numel[t] * hp.elem_size, fn = (uintptr_t)hp.t_numel[t] * 4,
+                            mn = master ? (uintptr_t)hp.t_numel[t] * 2 : 0;
+            if (ln && (!lp || !pa || !va || (master && !ma))) { kt_set_error("%s: NULL pointer for tensor %d", who, t); return KT_EINVAL; }
+            if (lp & emask) { kt_set_error("%s: tensor %d gradient not aligned to the element size", who, t); return KT_EALIGN; }
+            if ((pa | va) & 3u) { kt_set_error("%s: tensor %d parameters/momentum not 4-byte aligned", who, t); return KT_EALIGN; }
+            if (ma & 1u) { kt_set_error("%s: tensor %d model parameters not 2-byte aligned", who, t); return KT_EALIGN; }
+            if (overlap(pa, fn, va, fn) || overlap(pa, fn, lp, ln) || overlap(va, fn, lp, ln) || overlap(ma, mn, lp, ln) ||
+                overlap(ma, mn, pa, fn) || overlap(ma, mn, va, fn)) {
+                kt_set_error("%s: gradient, parameters, momentum and model parameters of tensor %d overlap", who, t);
+                return KT_EINVAL;
+            }
+            for (size_t k = 0; k < KP; ++k) {
+                const uintptr_t pp = vals[P0 + (size_t)b * KP + k];
+                if (overlap(pa, fn, pp, bbytes) || overlap(va, fn, pp, bbytes) || overlap(ma, mn, pp, bbytes)) {
+                    kt_set_error("%s: parameters, momentum or model parameters of tensor %d overlap peer %zu of bucket %d", who, t, k + 1, b);
+                    return KT_EINVAL;
+                }
+            }
+        }
+    }
+    st = ensure_device(p, s);
+    if (st != KT_OK) return st;
+    PtrSlot *slot = nullptr;
+    st = stage_pointers(p, vals.data(), vals.size(), s, &slot);
+    if (st != KT_OK) return st;
+    uint64_t *d = static_cast<uint64_t *>(slot->dev);
+    KtSgd a{scale, lr, momentum, weight_decay, first_step ? 1 : 0, resident ? p->dev_sgd : nullptr};
+    int e = kt_launch_fused_sgd(p->tb, hp.dt, tile0, ntiles, reinterpret_cast<const void *const *>(d),
+                                reinterpret_cast<const void *const *>(d + P0), K, w,
+                                reinterpret_cast<void *const *>(d + T), reinterpret_cast<void *const *>(d + 2 * T),
+                                master ? reinterpret_cast<void *const *>(d + 3 * T) : nullptr, a, vec, stream);
+    if (e != 0) { kt_set_error("%s: launch: %s", who, hipGetErrorString((hipError_t)e)); return KT_EHIP; }
+    return mark_used(p, slot, s);
+    KT_GUARD_END(who)
+}
+
+extern "C" kt_status kt_fused_step_sgd(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                                       const void *const *peer_bufs, int K, const float *weights, float scale,
+                                       void *const *param_ptrs, void *const *momentum_ptrs, void *const *model_ptrs,
+                                       float lr, float momentum, float weight_decay, int first_step, void *stream)
+{
+    return fused_sgd_impl(p, bucket, local_tensor_ptrs, peer_bufs, K, weights, scale, param_ptrs, momentum_ptrs,
+                          model_ptrs, lr, momentum, weight_decay, first_step, stream, "kt_fused_step_sgd", false);
+}
+
+extern "C" kt_status kt_fused_step_sgd_resident(kt_plan *p, int bucket, const void *const *local_tensor_ptrs,
+                                                const void *const *peer_bufs, int K, void *const *param_ptrs,
+                                                void *const *momentum_ptrs, void *const *model_ptrs, int first_step,
+                                                void *stream)
+{
+    return fused_sgd_impl(p, bucket, local_tensor_ptrs, peer_bufs, K, nullptr, 0.0f, param_ptrs, momentum_ptrs,
+                          model_ptrs, 0.0f, 0.0f, 0.0f, first_step, stream, "kt_fused_step_sgd_resident", true);
+}

@@ -97,6 +97,14 @@ int kt_launch_unpack_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                          void *const *d_model_ptrs /* NULL: no bf16 model copy */,
                          const KtSgd &a, bool vector_ok, void *stream);
 
+// The single pass from K gradient copies to updated parameters (kt_fused_sgd.hip).
+int kt_launch_fused_sgd(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
+                        int64_t ntiles, const void *const *d_local_ptrs,
+                        const void *const *d_peer_ptrs, int K, const KtWeights &w,
+                        void *const *d_param_ptrs, void *const *d_mom_ptrs,
+                        void *const *d_model_ptrs /* NULL: no bf16 model copy */,
+                        const KtSgd &a, bool vector_ok, void *stream);
+
 // ---- shared between the C ABI (kt_api.cpp) and the entry point that
 // allocates nothing (kt_static.hip) ------------------------------------------
 

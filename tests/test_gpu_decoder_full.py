@@ -5,7 +5,8 @@ over peer slot 0.
 
 The GPU path runs once (module fixture): pack, reduce, unpack-scale; the fused
 single pass; two steps of unpack fused with SGD (the second through the
-mixed-precision entry, which also writes the bf16 model copy).  The checker then goes through
+mixed-precision entry, which also writes the bf16 model copy); the same two
+steps through kt_fused_step_sgd (peer copies to parameters in one pass).  The checker then goes through
 the workload bucket by bucket.  Its inputs are the seeded tensors and peer
 buckets only: peer slot 0 is the checker's own pack of the local tensors, the
 reduced bucket is the checker's own reduce, and so on down the chain; nothing
@@ -13,8 +14,8 @@ the library wrote is fed back into it.  The checker is applied to contiguous
 element ranges on several host threads (every step is element-wise, so ranges
 are independent); its arithmetic is the single-threaded code as it stands.
 
-Bars: pack bit-exact; reduce, unpack, fused pass and both SGD steps
-bit-identical to checker mode S; reduce and unpack also within one bf16 ulp
+Bars: pack bit-exact; reduce, unpack, fused pass and both SGD steps (either
+way) bit-identical to checker mode S; reduce and unpack also within one bf16 ulp
 after binary32 accumulation of checker mode D (ulp_bf16(D) + K * 2^-24 *
 sum_k |w_k x_k| per element; scale 1.0 leaves the value unchanged)."""
 import os
@@ -137,10 +138,19 @@ def dec():
     # the second step through the mixed-precision entry: same update, plus the bf16 model copy
     model = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in w.numels]
     plan.kt_bucket_unpack_sgd_master(-1, slot0, SGD_SCALES[1], params, moms, model, LR, MU, WD, False)
+    say("[decoder] the same two steps in one pass each, from the local tensors and the peer buckets")
+    others = [peers[k][b] for b in range(nb) for k in range(1, K)]
+    fp = [t.clone() for t in p0]
+    fv = [torch.full((n,), float("nan"), device=DEV) for n in w.numels]
+    plan.kt_fused_step_sgd(-1, local, others, K, weights, SGD_SCALES[0], fp, fv, None, LR, MU, WD, True)
+    fp1, fv1 = [t.clone() for t in fp], [t.clone() for t in fv]
+    fmodel = [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in w.numels]
+    plan.kt_fused_step_sgd(-1, local, others, K, weights, SGD_SCALES[1], fp, fv, fmodel, LR, MU, WD, False)
     torch.cuda.synchronize()
     say("[decoder] device work done; %d host threads for the checker" % NTHREADS)
     yield dict(w=w, L=L, wts=wts, peers=peers, local=local, packed=packed, reduced=slot0, result=result, fused=fused,
-               p0=p0, p1=p1, v1=v1, p2=params, v2=moms, model=model, plan=plan)
+               p0=p0, p1=p1, v1=v1, p2=params, v2=moms, model=model, plan=plan,
+               fp1=fp1, fv1=fv1, fp2=fp, fv2=fv, fmodel=fmodel)
     torch.cuda.empty_cache()
 
 
@@ -190,7 +200,12 @@ def test_decoder_every_element_of_every_bucket(dec, group):
                                         ("momentum after step 1", dec["v1"][t], v1w[i]),
                                         ("parameters after step 2", dec["p2"][t], p2w[i]),
                                         ("momentum after step 2", dec["v2"][t], v2w[i]),
-                                        ("bf16 model copy after step 2", dec["model"][t], m2w[i])):
+                                        ("bf16 model copy after step 2", dec["model"][t], m2w[i]),
+                                        ("one pass: parameters after step 1", dec["fp1"][t], p1w[i]),
+                                        ("one pass: momentum after step 1", dec["fv1"][t], v1w[i]),
+                                        ("one pass: parameters after step 2", dec["fp2"][t], p2w[i]),
+                                        ("one pass: momentum after step 2", dec["fv2"][t], v2w[i]),
+                                        ("one pass: bf16 model copy after step 2", dec["fmodel"][t], m2w[i])):
                 got_s = host(dev_t)
                 assert same_bits(got_s, want_t), "SGD %s, tensor %d: %s" % (what, t, first_diff(got_s, want_t))
         say("[decoder] bucket %d: %d tensors, %d elements, %d of them differ from the double-accumulated definition "

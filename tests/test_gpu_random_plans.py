@@ -80,6 +80,10 @@ def test_random_plan(seed):
     moms = [torch.full((n,), float("nan"), device=DEV) for n in w.numels]
     hp, hv = [host(p) for p in params], [host(v) for v in moms]
     hb = [host(o) for o in outs]
+    # the first step also in one pass from the local tensors and the peer buckets
+    fp, fv = [p.clone() for p in params], [v.clone() for v in moms]
+    plan.kt_fused_step_sgd(-1, grads[0], [peers[k][b] for b in range(nb) for k in range(1, K)], K, weights, scale,
+                           fp, fv, None, 0.1, 0.9, 5e-4, True)
     for step in range(2):
         plan.kt_bucket_unpack_sgd(-1, outs, scale, params, moms, 0.1, 0.9, 5e-4, step == 0)
         torch.cuda.synchronize()
@@ -87,3 +91,6 @@ def test_random_plan(seed):
         for t in range(len(w.numels)):
             assert raw(host(params[t])).tobytes() == raw(hp[t]).tobytes(), ("sgd p", step, t)
             assert raw(host(moms[t])).tobytes() == raw(hv[t]).tobytes(), ("sgd v", step, t)
+            if step == 0:
+                assert raw(host(fp[t])).tobytes() == raw(hp[t]).tobytes(), ("one-pass sgd p", t)
+                assert raw(host(fv[t])).tobytes() == raw(hv[t]).tobytes(), ("one-pass sgd v", t)

@@ -373,6 +373,46 @@ def test_resident_sgd_scalars_argument_errors_without_gpu():
         p.kt_bucket_unpack_sgd_resident(-1, ok_b, ok_p, ok_v, ok_m[:1], False, stream=0)
 
 
+def test_fused_step_sgd_argument_errors_without_gpu():
+    p = kt.Plan([10, 20], "bf16", 0, 16)
+    g, pa, va, ma, peer = [1600, 3200], [16000, 32000], [48000, 64000], [80000, 96000], [409600]
+    w2 = [0.5, 0.5]
+
+    def call(**kw):
+        a = dict(bucket=-1, g=g, peers=peer, K=2, w=w2, pa=pa, va=va, ma=None)
+        a.update(kw)
+        return p.kt_fused_step_sgd(a["bucket"], a["g"], a["peers"], a["K"], a["w"], 1.0, a["pa"], a["va"], a["ma"],
+                                   0.1, 0.9, 0.0, True, stream=0)
+
+    cases = [
+        (dict(bucket=3), "KT_EINVAL"),
+        (dict(K=0), "KT_EINVAL"),
+        (dict(K=65), "KT_EINVAL"),
+        (dict(g=[0, 3200]), "KT_EINVAL"),                 # NULL gradient
+        (dict(g=[1601, 3200]), "KT_EALIGN"),              # gradient not element-aligned
+        (dict(pa=[16002, 32000]), "KT_EALIGN"),           # parameters not 4-byte aligned
+        (dict(ma=[80001, 96000]), "KT_EALIGN"),           # model copy not 2-byte aligned
+        (dict(peers=[0]), "KT_EINVAL"),                   # NULL peer
+        (dict(peers=[409601]), "KT_EALIGN"),
+        (dict(va=[16008, 64000]), "KT_EINVAL"),           # momentum over the parameters
+        (dict(pa=[1604, 32000]), "KT_EINVAL"),            # parameters over the gradient
+        (dict(ma=[16010, 96000]), "KT_EINVAL"),           # model copy over the parameters
+        (dict(pa=[409604, 32000]), "KT_EINVAL"),          # parameters over a peer bucket
+        (dict(w=None), "KT_EINVAL"),                      # no resident weights
+    ]
+    for kw, want in cases:
+        with pytest.raises(kt.KtError) as ei:
+            call(**kw)
+        assert ei.value.status_name == want, (kw, str(ei.value))
+    with pytest.raises(ValueError):
+        call(ma=ma[:1])
+    with pytest.raises(ValueError):
+        call(peers=[409600, 819200])
+    with pytest.raises(kt.KtError) as ei:                 # resident form: nothing set
+        p.kt_fused_step_sgd_resident(-1, g, peer, 2, pa, va, None, False, stream=0)
+    assert ei.value.status_name == "KT_EINVAL"
+
+
 def test_unpack_sgd_master_argument_errors_without_gpu():
     p = kt.Plan([10, 20], "bf16", 0, 16)
     ok_p, ok_v, ok_m, ok_b = [16000, 32000], [48000, 64000], [80000, 96000], [4096]
