@@ -40,8 +40,12 @@ __device__ __forceinline__ KtSgd resolve_sgd(KtSgd a)
 // bf16: a vector holds 8 elements = 32 bytes of p; the tile's reduced values go
 // through LDS (16 KiB) and come back in quads of 4 elements, so that every
 // access to p and v is one coalesced 16 bytes per lane.
+// FIRST (momentum not read) and MODEL (bf16 copy written) are compile-time here: as run-time
+// conditions inside the unrolled loops they split the loads into basic blocks with a wait at
+// every join, which serialises them.
 template <typename T> struct TileUpdate;
 template <> struct TileUpdate<float> {
+    template <bool FIRST, bool MODEL>
     static __device__ __forceinline__ void run(const u32x4 *g, u32x4 *, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a)
     {
         constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
@@ -50,8 +54,7 @@ template <> struct TileUpdate<float> {
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             pr[u] = ld_vec(p4 + u * KT_BLOCK + tid);
-            vr[u] = u32x4{0, 0, 0, 0};
-            if (!a.first) vr[u] = ld_vec(v4 + u * KT_BLOCK + tid);
+            vr[u] = FIRST ? u32x4{0, 0, 0, 0} : ld_vec(v4 + u * KT_BLOCK + tid);
         }
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
@@ -60,11 +63,12 @@ template <> struct TileUpdate<float> {
             sgd_quad(q, pr[u], vr[u], a);
             st_vec(p4 + u * KT_BLOCK + tid, pr[u]);
             st_vec(v4 + u * KT_BLOCK + tid, vr[u]);
-            if (m2) st_model_quad(m2 + u * KT_BLOCK + tid, pr[u]);
+            if (MODEL) st_model_quad(m2 + u * KT_BLOCK + tid, pr[u]);
         }
     }
 };
 template <> struct TileUpdate<uint16_t> {
+    template <bool FIRST, bool MODEL>
     static __device__ __forceinline__ void run(const u32x4 *g, u32x4 *lds, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a)
     {
         constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
@@ -83,8 +87,7 @@ template <> struct TileUpdate<uint16_t> {
             q[j].d[0] = t[0];
             q[j].d[1] = t[1];
             pr[j] = ld_vec(p4 + qi);
-            vr[j] = u32x4{0, 0, 0, 0};
-            if (!a.first) vr[j] = ld_vec(v4 + qi);
+            vr[j] = FIRST ? u32x4{0, 0, 0, 0} : ld_vec(v4 + qi);
         }
 #pragma unroll
         for (int j = 0; j < QPT; ++j) {
@@ -92,10 +95,26 @@ template <> struct TileUpdate<uint16_t> {
             sgd_quad(q[j], pr[j], vr[j], a);
             st_vec(p4 + qi, pr[j]);
             st_vec(v4 + qi, vr[j]);
-            if (m2) st_model_quad(m2 + qi, pr[j]);
+            if (MODEL) st_model_quad(m2 + qi, pr[j]);
         }
     }
 };
+
+// The update of a full solid tile, dispatched on the two uniform conditions.
+template <typename T>
+__device__ __forceinline__ void tile_update(const u32x4 *g, u32x4 *lds, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a_in)
+{
+    KtSgd a = a_in;
+    if (a_in.first) {
+        a.first = 1;
+        if (m2) TileUpdate<T>::template run<true, true>(g, lds, p4, v4, m2, a);
+        else TileUpdate<T>::template run<true, false>(g, lds, p4, v4, m2, a);
+    } else {
+        a.first = 0;
+        if (m2) TileUpdate<T>::template run<false, true>(g, lds, p4, v4, m2, a);
+        else TileUpdate<T>::template run<false, false>(g, lds, p4, v4, m2, a);
+    }
+}
 
 // Everything that is not a full, aligned solid tile: vector by vector, with a
 // loop over the peers; vectors that are not wholly inside one tensor at aligned
@@ -267,7 +286,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_kernel(KtDeviceTables t
 #pragma unroll
         for (int u = 0; u < VPT; ++u) asm volatile("" : "+v"(red[u]));
         __builtin_amdgcn_sched_barrier(0);
-        TileUpdate<T>::run(red, lds.red, st.p4, st.v4, st.m2, a);
+        tile_update<T>(red, lds.red, st.p4, st.v4, st.m2, a);
         return;
     }
     fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, 1);
@@ -299,7 +318,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_any_kernel(KtDeviceTabl
         u32x4 red[VPT];
 #pragma unroll
         for (int u = 0; u < VPT; ++u) red[u] = acc[u].finish();
-        TileUpdate<T>::run(red, lds.red, st.p4, st.v4, st.m2, a);
+        tile_update<T>(red, lds.red, st.p4, st.v4, st.m2, a);
         return;
     }
     fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, vec_ok);
