@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_sgd_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip",
                   "kt_sgd.hip", "kt_fused_sgd.hip")
-TRAFFIC_SOURCES_SHA = "311403823b51f89a"
-TRAFFIC_BYTES = {"decoder_1p3b": 23704862575, "vit_b16": 3119145150}
+TRAFFIC_SOURCES_SHA = "483da32edff5fd38"
+TRAFFIC_BYTES = {"decoder_1p3b": 23704846324, "vit_b16": 3119142077}
 
 
 def measured_traffic(workload):
@@ -178,6 +178,7 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
     ms_graph = None
     try:
         graph = torch.cuda.CUDAGraph()
+        step(st)        # the calls above used more pointer sets than the library keeps resident (8)
         torch.cuda.synchronize()
         with torch.cuda.graph(graph):
             step(st)
