@@ -1,7 +1,7 @@
 // The C ABI used from a plain HIP program: no Python, no PyTorch, device memory from hipMalloc,
 // the default stream and a stream of its own.  Runs pack -> K-way weighted reduce -> unpack-scale,
-// the fused single pass, the entry point that allocates nothing and SGD on unpack on a small
-// ragged gradient set and compares every element with the CPU checker's C functions (strict
+// the fused single pass, the entry point that allocates nothing, SGD on unpack and the one-pass
+// reduce + SGD (by value, then with resident weights and scalars) on a small ragged gradient set and compares every element with the CPU checker's C functions (strict
 // binary32 mode: bit-identical).  Test infrastructure: links libkt.so and libkt_oracle.so.
 // Prints "ok ..." and exits 0, or names the first mismatch and exits 1.
 #include <hip/hip_runtime.h>
@@ -156,6 +156,45 @@ int main()
         }
     }
 
+    // the same two steps in one pass from the local tensors and the peer buckets, with the weights and the
+    // optimizer scalars resident on the device for the second step
+    std::vector<void *> par2(T), mom2(T);
+    std::vector<std::vector<float>> hp2(T), hv2(T);
+    g_state = 0x13198A2E03707344ull;
+    for (int t = 0; t < T; ++t) {
+        HIP_OK(hipMalloc(&par2[t], (size_t)numel[t] * 4));
+        HIP_OK(hipMalloc(&mom2[t], (size_t)numel[t] * 4));
+        hp2[t].resize((size_t)numel[t]);
+        hv2[t].assign((size_t)numel[t], 0.0f);
+        for (float &x : hp2[t]) x = next_value() * 100.0f;
+        HIP_OK(hipMemcpy(par2[t], hp2[t].data(), (size_t)numel[t] * 4, hipMemcpyHostToDevice));
+        HIP_OK(hipMemset(mom2[t], 0xFF, (size_t)numel[t] * 4));
+    }
+    for (int step = 0; step < 2; ++step) {
+        const float lr = step == 0 ? 0.1f : 0.01f;
+        if (step == 0) {
+            KT_OKAY(kt_fused_step_sgd(plan, KT_ALL_BUCKETS, dg[0].data(), others.data(), K, w, scale, par2.data(), mom2.data(),
+                                      nullptr, lr, 0.9f, 5e-4f, 1, side));
+        } else {
+            KT_OKAY(kt_plan_set_weights(plan, w, K, side));
+            KT_OKAY(kt_plan_set_sgd(plan, scale, lr, 0.9f, 5e-4f, side));
+            KT_OKAY(kt_fused_step_sgd_resident(plan, KT_ALL_BUCKETS, dg[0].data(), others.data(), K, par2.data(), mom2.data(),
+                                               nullptr, 0, side));
+        }
+        HIP_OK(hipStreamSynchronize(side));
+        for (int t = 0; t < T; ++t) {
+            const size_t n = (size_t)numel[t];
+            const float *xs[K] = {hg[0][t].data(), hg[1][t].data(), hg[2][t].data()};
+            std::vector<float> sum(n), got(n);
+            kto_reduce_f32_S(xs, w, K, (int64_t)n, sum.data());
+            kto_sgd_f32_S(sum.data(), (int64_t)n, scale, hp2[t].data(), hv2[t].data(), lr, 0.9f, 5e-4f, step == 0);
+            HIP_OK(hipMemcpy(got.data(), par2[t], n * 4, hipMemcpyDeviceToHost));
+            if (!same(got, hp2[t], "one-pass SGD parameters", t)) ++bad;
+            HIP_OK(hipMemcpy(got.data(), mom2[t], n * 4, hipMemcpyDeviceToHost));
+            if (!same(got, hv2[t], "one-pass SGD momentum", t)) ++bad;
+        }
+    }
+
     // errors come back as codes, with a message, and leave the plan usable
     if (kt_weighted_reduce(plan, nb, peers.data(), K, w, red.data(), nullptr) != KT_EINVAL || !*kt_last_error()) { printf("bad bucket not refused\n"); ++bad; }
     KT_OKAY(kt_weighted_reduce(plan, 0, peers.data(), K, w, red.data(), nullptr));
@@ -163,7 +202,7 @@ int main()
     KT_OKAY(kt_plan_destroy(plan));
     HIP_OK(hipStreamDestroy(side));
     if (bad) { printf("%d mismatches\n", bad); return 1; }
-    printf("ok %s: %d tensors, %d buckets, K=%d; chained, fused, no-allocation and SGD paths equal the checker\n",
+    printf("ok %s: %d tensors, %d buckets, K=%d; chained, fused, no-allocation, SGD and one-pass SGD paths equal the checker\n",
            kt_version(), T, nb, K);
     return 0;
 }
