@@ -45,10 +45,9 @@ __device__ __forceinline__ KtSgd resolve_sgd(KtSgd a)
 // every join, which serialises them.
 template <typename T> struct TileUpdate;
 template <> struct TileUpdate<float> {
-    template <bool FIRST, bool MODEL>
+    template <int VPT, bool FIRST, bool MODEL>
     static __device__ __forceinline__ void run(const u32x4 *g, u32x4 *, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a)
     {
-        constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
         const int tid = threadIdx.x;
         u32x4 pr[VPT], vr[VPT];
 #pragma unroll
@@ -68,10 +67,9 @@ template <> struct TileUpdate<float> {
     }
 };
 template <> struct TileUpdate<uint16_t> {
-    template <bool FIRST, bool MODEL>
+    template <int VPT, bool FIRST, bool MODEL>
     static __device__ __forceinline__ void run(const u32x4 *g, u32x4 *lds, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a)
     {
-        constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
         constexpr int QPT = 2 * VPT;          // quads per lane
         const int tid = threadIdx.x;
 #pragma unroll
@@ -100,21 +98,34 @@ template <> struct TileUpdate<uint16_t> {
     }
 };
 
-// The update of a full solid tile, dispatched on the two uniform conditions.
-template <typename T>
+// The update of a workgroup's share of a full solid tile (VPT reduced vectors per lane; p4, v4,
+// m2 point at the share's first quad), dispatched on the two uniform conditions.
+template <typename T, int VPT>
 __device__ __forceinline__ void tile_update(const u32x4 *g, u32x4 *lds, u32x4 *p4, u32x4 *v4, u32x2 *m2, const KtSgd &a_in)
 {
     KtSgd a = a_in;
     if (a_in.first) {
         a.first = 1;
-        if (m2) TileUpdate<T>::template run<true, true>(g, lds, p4, v4, m2, a);
-        else TileUpdate<T>::template run<true, false>(g, lds, p4, v4, m2, a);
+        if (m2) TileUpdate<T>::template run<VPT, true, true>(g, lds, p4, v4, m2, a);
+        else TileUpdate<T>::template run<VPT, true, false>(g, lds, p4, v4, m2, a);
     } else {
         a.first = 0;
-        if (m2) TileUpdate<T>::template run<false, true>(g, lds, p4, v4, m2, a);
-        else TileUpdate<T>::template run<false, false>(g, lds, p4, v4, m2, a);
+        if (m2) TileUpdate<T>::template run<VPT, false, true>(g, lds, p4, v4, m2, a);
+        else TileUpdate<T>::template run<VPT, false, false>(g, lds, p4, v4, m2, a);
     }
 }
+
+// How a 16 KiB tile is shared out.  Measured on flat buffers at K = 8: 16 elements per lane and
+// workgroup (4 quads of p and of v) is the optimum for both element types -- binary32: the whole
+// tile, 74.8 % of 8 TB/s against 72.4 % for half a tile; bf16: half a tile, 74.5 % against 71.2 %
+// for the whole tile (the read-dominated first half wants many loads in flight, the second half,
+// which writes what it reads, little work per workgroup).
+template <typename T> struct FsgdShape {
+    static constexpr int TILE_VPT = KT_TILE_VECS / KT_BLOCK;
+    static constexpr int VPT = (sizeof(T) == 2 && TILE_VPT % 2 == 0) ? TILE_VPT / 2 : TILE_VPT;   // vectors per lane
+    static constexpr int SPLIT = TILE_VPT / VPT;                                                    // workgroups per tile
+    static constexpr int QUADS = VPT * KT_BLOCK * Elem<T>::VE / 4;                                 // quads per share
+};
 
 // Everything that is not a full, aligned solid tile: vector by vector, with a
 // loop over the peers; vectors that are not wholly inside one tensor at aligned
@@ -124,13 +135,13 @@ __device__ __forceinline__ void tile_update(const u32x4 *g, u32x4 *lds, u32x4 *p
 template <typename T, bool DEVW, typename V>
 __device__ __forceinline__ void fsgd_generic(const V &tv, int nt, const TileGeom &g, int64_t b_n,
                                              const void *const *pp, int K, const KtWeights &wts, const KtSgd &a,
-                                             void *const *mom, void *const *model, int vec_ok)
+                                             void *const *mom, void *const *model, int vec_ok, int part, int parts)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int PV = SgdVec<T>::PV;
     const int nvec = (int)((g.end - g.start + VE - 1) / VE);
 #pragma unroll 1
-    for (int v = threadIdx.x; v < nvec; v += KT_BLOCK) {
+    for (int v = part * KT_BLOCK + threadIdx.x; v < nvec; v += parts * KT_BLOCK) {
         const int64_t e0 = g.start + (int64_t)v * VE;
         int i = find_owner_v(tv, nt, e0);
         if (vec_ok && i >= 0 && e0 + VE <= b_n) {
@@ -226,7 +237,7 @@ union FsgdLds {
 template <typename T, bool DEVW>
 __device__ __forceinline__ void fsgd_other_tile(LdsTable &lds, const KtDeviceTables &tb, const KtTile &tl,
                                                 const TileGeom &g, const FsgdArgs &f, const void *const *pp, int K,
-                                                const KtWeights &wts, const KtSgd &a, int vec_ok)
+                                                const KtWeights &wts, const KtSgd &a, int vec_ok, int part, int parts)
 {
     const int nt = tl.nt == 0 ? 1 : tl.nt;
     const int64_t b_n = tb.b_elems[g.bucket];
@@ -235,39 +246,42 @@ __device__ __forceinline__ void fsgd_other_tile(LdsTable &lds, const KtDeviceTab
     void *const *model = f.model_ptrs ? f.model_ptrs + tl.t0 : nullptr;
     if (nt <= KT_LDS_TENSORS) {
         const LdsView tv = stage_lds(lds, tb, f.local_ptrs, prm, tl.t0, nt);
-        fsgd_generic<T, DEVW>(tv, nt, g, b_n, pp, K, wts, a, mom, model, vec_ok);
+        fsgd_generic<T, DEVW>(tv, nt, g, b_n, pp, K, wts, a, mom, model, vec_ok, part, parts);
     } else {
         const GlobalView tv = global_view(tb, f.local_ptrs, prm, tl.t0);
-        fsgd_generic<T, DEVW>(tv, nt, g, b_n, pp, K, wts, a, mom, model, vec_ok);
+        fsgd_generic<T, DEVW>(tv, nt, g, b_n, pp, K, wts, a, mom, model, vec_ok, part, parts);
     }
 }
 
-// K = 1..8, 16-byte aligned buckets.  Full solid tiles: 4 vectors x K copies =
-// up to 32 loads in flight per lane, as in the reduce, then the update.
+// K = 1..8, 16-byte aligned buckets.  SPLIT workgroups share a tile; on a full solid tile each
+// has VPT vectors x K copies in flight per lane (32 loads for binary32, 16 for bf16 at K = 8), as
+// in the reduce, then the update of its share.
 template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_kernel(KtDeviceTables tb, int64_t tile0, FsgdArgs f,
                                                                 KtWeights wts, KtSgd a_in)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
-    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    constexpr int VPT = FsgdShape<T>::VPT, SPLIT = FsgdShape<T>::SPLIT, QUADS = FsgdShape<T>::QUADS;
     __shared__ FsgdLds lds;
 
     const KtSgd a = resolve_sgd(a_in);
-    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const int part = SPLIT == 1 ? 0 : (int)(blockIdx.x % SPLIT);
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x / SPLIT];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const int tid = threadIdx.x;
     const void *const *pp = f.peer_ptrs + (int64_t)g.bucket * (K - 1);   // peers 1..K-1 of this bucket
 
     const SolidTile<T> st = solid_tile<T>(tb, tl, g, f, 1);
     if (st.ok) {
+        const int v0 = part * VPT * KT_BLOCK + tid;     // the lane's first vector in the tile
         u32x4 r[VPT][K];
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
-            r[u][0] = ld_vec(reinterpret_cast<const u32x4 *>(st.src) + u * KT_BLOCK + tid);
+            r[u][0] = ld_vec(reinterpret_cast<const u32x4 *>(st.src) + v0 + u * KT_BLOCK);
 #pragma unroll
             for (int k = 1; k < K; ++k)
-                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k - 1]) + g.start) + u * KT_BLOCK + tid);
+                r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(reinterpret_cast<const T *>(pp[k - 1]) + g.start) + v0 + u * KT_BLOCK);
         }
         // keep every load above the arithmetic: all of them are in flight together
         __builtin_amdgcn_sched_barrier(0);
@@ -286,10 +300,11 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_kernel(KtDeviceTables t
 #pragma unroll
         for (int u = 0; u < VPT; ++u) asm volatile("" : "+v"(red[u]));
         __builtin_amdgcn_sched_barrier(0);
-        tile_update<T>(red, lds.red, st.p4, st.v4, st.m2, a);
+        tile_update<T, VPT>(red, lds.red, st.p4 + part * QUADS, st.v4 + part * QUADS,
+                            st.m2 ? st.m2 + part * QUADS : nullptr, a);
         return;
     }
-    fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, 1);
+    fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, 1, part, SPLIT);
 }
 
 // Any K (1..64) and any alignment: full solid tiles of aligned buckets take the
@@ -318,10 +333,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_any_kernel(KtDeviceTabl
         u32x4 red[VPT];
 #pragma unroll
         for (int u = 0; u < VPT; ++u) red[u] = acc[u].finish();
-        tile_update<T>(red, lds.red, st.p4, st.v4, st.m2, a);
+        tile_update<T, VPT>(red, lds.red, st.p4, st.v4, st.m2, a);
         return;
     }
-    fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, vec_ok);
+    fsgd_other_tile<T, DEVW>(lds.table, tb, tl, g, f, pp, K, wts, a, vec_ok, 0, 1);
 }
 
 template <typename T, bool DEVW>
@@ -333,14 +348,24 @@ hipError_t launch_fused_sgd_t(const KtDeviceTables &tb, int64_t tile0, int64_t n
         kt_fused_sgd_any_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, f, K, w, a, vector_ok ? 1 : 0);
         return hipGetLastError();
     }
-    switch (K) {
+    // SPLIT workgroups per tile; a grid may not hold 2^32 or more lanes: very large plans go in several launches
+    constexpr int SPLIT = FsgdShape<T>::SPLIT;
+    const int64_t per_launch = (((int64_t)1 << 32) / KT_BLOCK - 1) / SPLIT;
+    for (int64_t done = 0; done < ntiles; done += per_launch) {
+        const int64_t now = ntiles - done < per_launch ? ntiles - done : per_launch;
+        const dim3 g2((unsigned)(now * SPLIT));
+        const int64_t t0 = tile0 + done;
+        switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_fused_sgd_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, f, w, a); break;
-        KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
+    case KK: kt_fused_sgd_kernel<T, KK, DEVW><<<g2, block, 0, s>>>(tb, t0, f, w, a); break;
+            KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
-    default: return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 }  // namespace
