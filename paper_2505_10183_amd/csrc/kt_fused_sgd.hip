@@ -115,16 +115,24 @@ __device__ __forceinline__ void tile_update(const u32x4 *g, u32x4 *lds, u32x4 *p
     }
 }
 
-// How a 16 KiB tile is shared out.  Measured on flat buffers at K = 8: 16 elements per lane and
-// workgroup (4 quads of p and of v) is the optimum for both element types -- binary32: the whole
-// tile, 74.8 % of 8 TB/s against 72.4 % for half a tile; bf16: half a tile, 74.5 % against 71.2 %
-// for the whole tile (the read-dominated first half wants many loads in flight, the second half,
-// which writes what it reads, little work per workgroup).
+// How a 16 KiB tile is shared out: one 16-byte vector of every copy per lane and workgroup, i.e.
+// 4 workgroups per tile.  With the tensors in allocations of their own (not congruent with the
+// bucket's tiles) this measured best for both element types: binary32 73 % of 8 TB/s against
+// 70 % for half or a whole tile per workgroup, bf16 71.6 % against 71 %.  The second half of the
+// kernel writes what it reads and, like the copy kernels, wants little work per workgroup.
+// KT_FSGD_VPT_F32 / KT_FSGD_VPT_BF16 override the vectors per lane and workgroup for measurement.
+#ifndef KT_FSGD_VPT_F32
+#define KT_FSGD_VPT_F32 1
+#endif
+#ifndef KT_FSGD_VPT_BF16
+#define KT_FSGD_VPT_BF16 1
+#endif
 template <typename T> struct FsgdShape {
     static constexpr int TILE_VPT = KT_TILE_VECS / KT_BLOCK;
-    static constexpr int VPT = (sizeof(T) == 2 && TILE_VPT % 2 == 0) ? TILE_VPT / 2 : TILE_VPT;   // vectors per lane
-    static constexpr int SPLIT = TILE_VPT / VPT;                                                    // workgroups per tile
-    static constexpr int QUADS = VPT * KT_BLOCK * Elem<T>::VE / 4;                                 // quads per share
+    static constexpr int VPT = sizeof(T) == 2 ? KT_FSGD_VPT_BF16 : KT_FSGD_VPT_F32;   // vectors per lane and workgroup
+    static constexpr int SPLIT = TILE_VPT / VPT;                                      // workgroups per tile
+    static constexpr int QUADS = VPT * KT_BLOCK * Elem<T>::VE / 4;                   // quads per share
+    static_assert(VPT >= 1 && TILE_VPT % VPT == 0, "a tile is shared out in equal parts");
 };
 
 // Everything that is not a full, aligned solid tile: vector by vector, with a
@@ -254,8 +262,7 @@ __device__ __forceinline__ void fsgd_other_tile(LdsTable &lds, const KtDeviceTab
 }
 
 // K = 1..8, 16-byte aligned buckets.  SPLIT workgroups share a tile; on a full solid tile each
-// has VPT vectors x K copies in flight per lane (32 loads for binary32, 16 for bf16 at K = 8), as
-// in the reduce, then the update of its share.
+// has VPT vectors x K copies in flight per lane, then the update of its share.
 template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_sgd_kernel(KtDeviceTables tb, int64_t tile0, FsgdArgs f,
                                                                 KtWeights wts, KtSgd a_in)
