@@ -1,7 +1,17 @@
 // HIP kernels for gfx950: the fused single pass (pack + reduce + unpack-scale in one kernel).
 #include "kt_device.h"
 
+// Vectors per lane and workgroup on a tile (KT_TILE_VECS / KT_BLOCK = the whole tile to one
+// workgroup); smaller values share the tile between several workgroups.
+#ifndef KT_FUSED_VPT
+#define KT_FUSED_VPT (KT_TILE_VECS / KT_BLOCK)
+#endif
+
 namespace {
+
+constexpr int FUSED_VPT = KT_FUSED_VPT;
+constexpr int FUSED_SPLIT = (KT_TILE_VECS / KT_BLOCK) / FUSED_VPT;
+static_assert(FUSED_VPT >= 1 && (KT_TILE_VECS / KT_BLOCK) % FUSED_VPT == 0, "a tile is shared out in equal parts");
 
 // ---- fused single pass: tensors + peer buckets -> scaled tensors ------------
 // out_t[i] = scale * round(sum_k w_k x_k), where x_0 is read straight from the
@@ -18,18 +28,19 @@ namespace {
 // wholly inside one tensor at 16-byte aligned addresses go element by element.
 template <typename T, int K, typename V>
 __device__ __forceinline__ void fused_mixed(const V &tv, int nt, const TileGeom &g, int64_t b_n,
-                                            const T *const *x, const float *w, float scale)
+                                            const T *const *x, const float *w, float scale, int part)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int MB = K <= 4 ? 4 : 2;
+    constexpr int STEP = FUSED_SPLIT * KT_BLOCK;      // distance between two vectors of one lane
     const int nvec = (int)((g.end - g.start + VE - 1) / VE);
 #pragma unroll 1
-    for (int v0 = threadIdx.x; v0 < nvec; v0 += MB * KT_BLOCK) {
+    for (int v0 = part * KT_BLOCK + threadIdx.x; v0 < nvec; v0 += MB * STEP) {
         u32x4 r[MB][K];
         uintptr_t where[MB];      // destination of a whole vector; 0 = none, 1 = element-wise
 #pragma unroll
         for (int j = 0; j < MB; ++j) {
-            const int v = v0 + j * KT_BLOCK;
+            const int v = v0 + j * STEP;
             where[j] = 0;
             if (v < nvec) {
                 where[j] = 1;
@@ -59,7 +70,7 @@ __device__ __forceinline__ void fused_mixed(const V &tv, int nt, const TileGeom 
                 for (int k = 1; k < K; ++k) acc.add(r[j][k], w[k]);
                 st_vec(reinterpret_cast<void *>(where[j]), scale_vec<T>(acc.finish(), scale));
             } else if (where[j] == 1) {
-                const int64_t e0 = g.start + (int64_t)(v0 + j * KT_BLOCK) * VE;
+                const int64_t e0 = g.start + (int64_t)(v0 + j * STEP) * VE;
                 int i = find_owner_v(tv, nt, e0);
 #pragma unroll 1
                 for (int q = 0; q < VE; ++q) {
@@ -87,11 +98,12 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
-    constexpr int VPT = KT_TILE_VECS / KT_BLOCK;
+    constexpr int VPT = FUSED_VPT, SPLIT = FUSED_SPLIT;
     constexpr int KP = K > 1 ? K - 1 : 1;
     __shared__ LdsTable lds;
 
-    const KtTile tl = tb.tiles[tile0 + blockIdx.x];
+    const int part = SPLIT == 1 ? 0 : (int)(blockIdx.x % SPLIT);
+    const KtTile tl = tb.tiles[tile0 + blockIdx.x / SPLIT];
     const TileGeom g = tile_geom(tl, tb.b_elems, TILE_ELEMS);
     const int tid = threadIdx.x;
 
@@ -110,13 +122,14 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
         if (((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15u) == 0) {
             const int nvec = (int)((g.end - g.start) / VE);
             if (nvec == KT_TILE_VECS) {
+                const int v0 = part * VPT * KT_BLOCK + tid;     // the lane's first vector in the tile
                 u32x4 r[VPT][K];
 #pragma unroll
                 for (int u = 0; u < VPT; ++u) {
-                    r[u][0] = ld_vec(reinterpret_cast<const u32x4 *>(src) + u * KT_BLOCK + tid);
+                    r[u][0] = ld_vec(reinterpret_cast<const u32x4 *>(src) + v0 + u * KT_BLOCK);
 #pragma unroll
                     for (int k = 1; k < K; ++k)
-                        r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + u * KT_BLOCK + tid);
+                        r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v0 + u * KT_BLOCK);
                 }
 #pragma unroll
                 for (int u = 0; u < VPT; ++u) {
@@ -124,11 +137,11 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
                     acc.first(r[u][0], w[0]);
 #pragma unroll
                     for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
-                    st_vec(reinterpret_cast<u32x4 *>(dst) + u * KT_BLOCK + tid, scale_vec<T>(acc.finish(), scale));
+                    st_vec(reinterpret_cast<u32x4 *>(dst) + v0 + u * KT_BLOCK, scale_vec<T>(acc.finish(), scale));
                 }
             } else {
 #pragma unroll 1
-                for (int v = tid; v < nvec; v += KT_BLOCK) {
+                for (int v = part * KT_BLOCK + tid; v < nvec; v += SPLIT * KT_BLOCK) {
                     Acc<T> acc;
                     acc.first(ld_vec(reinterpret_cast<const u32x4 *>(src) + v), w[0]);
 #pragma unroll
@@ -146,10 +159,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
     const void *const *op = reinterpret_cast<const void *const *>(out_ptrs);
     if (nt <= KT_LDS_TENSORS) {
         const LdsView tv = stage_lds(lds, tb, local_ptrs, op, tl.t0, nt);
-        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale);
+        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale, part);
     } else {
         const GlobalView tv = global_view(tb, local_ptrs, op, tl.t0);
-        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale);
+        fused_mixed<T, K>(tv, nt, g, b_n, x, w, scale, part);
     }
 }
 
@@ -279,14 +292,23 @@ hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntile
         kt_fused_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
         return hipGetLastError();
     }
-    switch (K) {
+    // FUSED_SPLIT workgroups per tile; a grid may not hold 2^32 or more lanes: very large plans go in several launches
+    const int64_t per_launch = (((int64_t)1 << 32) / KT_BLOCK - 1) / FUSED_SPLIT;
+    for (int64_t done = 0; done < ntiles; done += per_launch) {
+        const int64_t now = ntiles - done < per_launch ? ntiles - done : per_launch;
+        const dim3 g2((unsigned)(now * FUSED_SPLIT));
+        const int64_t t0 = tile0 + done;
+        switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_fused_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, w, scale, outs); break;
-        KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
+    case KK: kt_fused_kernel<T, KK, DEVW><<<g2, block, 0, s>>>(tb, t0, locals, peers, w, scale, outs); break;
+            KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
-    default: return hipErrorInvalidValue;
+        default: return hipErrorInvalidValue;
+        }
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 }  // namespace
