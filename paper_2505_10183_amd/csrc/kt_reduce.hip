@@ -29,6 +29,12 @@
 #ifndef KT_REDUCE_XCD
 #define KT_REDUCE_XCD 0
 #endif
+//   KT_REDUCE_CHUNK   0: all K copies of the lane's 4 vectors in flight together
+//                     c: the copies taken c at a time, accumulators kept in registers (fewer
+//                        registers, more workgroups per CU, fewer loads in flight per lane)
+#ifndef KT_REDUCE_CHUNK
+#define KT_REDUCE_CHUNK 0
+#endif
 
 namespace {
 
@@ -77,6 +83,36 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
     const int64_t n = g.end - g.start;
     const int nvec = (int)(n / VE);
 
+#if KT_REDUCE_CHUNK > 0
+    if (nvec == KT_TILE_VECS && K > KT_REDUCE_CHUNK) {
+        constexpr int C = KT_REDUCE_CHUNK;
+        Acc<T> acc[VPT];
+#pragma unroll
+        for (int k0 = 0; k0 < K; k0 += C) {
+            u32x4 r[VPT][C];
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    if (k0 + j < K) r[u][j] = ld_vec(reinterpret_cast<const u32x4 *>(x[k0 + j < K ? k0 + j : 0]) + u * KT_BLOCK + tid);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+#pragma unroll
+                for (int j = 0; j < C; ++j)
+                    if (k0 + j < K) {
+                        if (k0 + j == 0) acc[u].first(r[u][j], w[0]); else acc[u].add(r[u][j], w[k0 + j < K ? k0 + j : 0]);
+                    }
+#pragma unroll
+            for (int u = 0; u < VPT; ++u)
+#pragma unroll
+                for (int c = 0; c < (int)(sizeof(acc[u].a) / sizeof(float)); ++c) asm volatile("" : "+v"(acc[u].a[c]));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc[u].finish());
+    } else
+#endif
     if (nvec == KT_TILE_VECS) {
         u32x4 r[VPT][K];
 #if KT_REDUCE_ISSUE == 1
