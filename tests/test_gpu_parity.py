@@ -501,6 +501,60 @@ def test_pointer_churn_and_streams():
         assert all(bool((t == float(r)).all()) for t in o2)
 
 
+def test_two_host_threads_share_a_plan():
+    """Two host threads, each with a stream of its own, call into one plan at
+    the same time with pointer sets of their own (the library serialises calls
+    on a plan; tables are evicted under both threads); every result is checked."""
+    import threading
+    w = wl.ragged_workload(dtype="bf16", K=3, seed=56, n_tensors=30)
+    plan = kt.Plan(w.numels, "bf16", w.bucket_cap_bytes, 16)
+    nb = plan.num_buckets
+    wts = np.array([0.5, 0.25, 0.25], np.float32)
+    grads = [wl.gradient_set(w, k, DEV) for k in range(3)]
+    plan.kt_bucket_pack(-1, grads[0], [torch.empty(n, dtype=torch.bfloat16, device=DEV) for n in plan.bucket_elems()])
+    torch.cuda.synchronize()
+    results, errors = {}, []
+
+    def worker(tid):
+        try:
+            torch.cuda.set_device(0)
+            st = torch.cuda.Stream()
+            mine = []
+            for r in range(25):
+                with torch.cuda.stream(st):
+                    peers = [[wl.flat_normal(n, "bf16", 1e-3, 9000 + 1000 * tid + 30 * r + 10 * k + b, DEV)
+                              for b, n in enumerate(plan.bucket_elems())] for k in range(3)]
+                    outs = [torch.empty_like(t) for t in peers[0]]
+                    res = [torch.empty_like(t) for t in grads[0]]
+                    plan.kt_weighted_reduce(-1, [peers[k][b] for b in range(nb) for k in range(3)], 3, list(wts), outs,
+                                            stream=st)
+                    plan.kt_bucket_unpack_scale(-1, outs, 0.5, res, stream=st)
+                mine.append((peers, outs, res))
+            st.synchronize()
+            results[tid] = mine
+        except Exception as exc:          # noqa: BLE001
+            errors.append((tid, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    L = oracle.assign_buckets(w.numels, 2, w.bucket_cap_bytes, 16)
+    for tid in range(2):
+        for r, (peers, outs, res) in enumerate(results[tid]):
+            if r % 6:
+                continue
+            hb = [oracle.weighted_reduce([host(peers[k][b]) for k in range(3)], wts, "bf16", "S") for b in range(nb)]
+            for b in range(nb):
+                assert host(outs[b]).tobytes() == hb[b].tobytes(), (tid, r, b)
+            want = oracle.unpack_scale(L, hb, w.numels, 0.5, "bf16", "S")
+            for t in range(len(w.numels)):
+                assert host(res[t]).tobytes() == want[t].tobytes(), (tid, r, t)
+
+
 def test_edge_shapes():
     """Zero-size tensors, a one-element plan, a bucket of exactly one tile, the
     maximum peer count, and an empty plan."""

@@ -4,7 +4,8 @@ phase 1 and 2): plan shares -> pack the K peers' gradients -> K-way weighted
 reduce -> SGD on unpack -> re-plan.  The CPU checker runs the same loop; shares
 and weights must agree exactly and parameters and momentum bit for bit after
 every step (checker mode S), whichever way the step is launched: chained calls,
-the fused pass followed by a separate SGD unpack, per bucket or batched."""
+the fused pass followed by a separate SGD unpack, per bucket or batched, or the
+one-pass call from the K gradient copies to the parameters."""
 import sys
 
 import numpy as np
@@ -38,6 +39,8 @@ def test_steps_with_online_replanning(dtype):
     params = [torch.randn(n, generator=gen, device=DEV) for n in w.numels]
     moms = [torch.zeros(n, device=DEV) for n in w.numels]
     hp, hv = [host(p) for p in params], [host(v) for v in moms]
+    # a second replica of the model state, advanced by the one-pass call (peer copies -> parameters)
+    params1, moms1 = [p.clone() for p in params], [v.clone() for v in moms]
     slots = [[torch.empty(n, dtype=tdtype(dtype), device=DEV) for n in elems] for _ in range(K)]
     red = [torch.empty(n, dtype=tdtype(dtype), device=DEV) for n in elems]
     grad_out = [torch.empty(n, dtype=tdtype(dtype), device=DEV) for n in w.numels]
@@ -59,6 +62,8 @@ def test_steps_with_online_replanning(dtype):
         plan.kt_bucket_unpack_sgd(-1, red, 1.0, params, moms, lr, mu, wd, step == 0)
         # the fused pass gives the averaged gradient itself (what a framework would hand to its own optimizer)
         plan.kt_fused_step(-1, grads[0], others, K, weights, 1.0, grad_out)
+        # ... and the one-pass form applies the update straight from the K copies
+        plan.kt_fused_step_sgd(-1, grads[0], others, K, weights, 1.0, params1, moms1, None, lr, mu, wd, step == 0)
         torch.cuda.synchronize()
         packed = [oracle.pack(L, hg[k], dtype) for k in range(K)]
         reduced = [oracle.weighted_reduce([packed[k][b] for k in range(K)], wts, dtype, "S") for b in range(nb)]
@@ -68,6 +73,8 @@ def test_steps_with_online_replanning(dtype):
             assert raw(host(params[t])).tobytes() == raw(hp[t]).tobytes(), ("parameters", step, t)
             assert raw(host(moms[t])).tobytes() == raw(hv[t]).tobytes(), ("momentum", step, t)
             assert raw(host(grad_out[t])).tobytes() == raw(want_g[t]).tobytes(), ("fused gradient", step, t)
+            assert raw(host(params1[t])).tobytes() == raw(hp[t]).tobytes(), ("one-pass parameters", step, t)
+            assert raw(host(moms1[t])).tobytes() == raw(hv[t]).tobytes(), ("one-pass momentum", step, t)
         # measured step times: samples / speed, with device 1 slowing down over time
         speed[1] *= 0.8
         times = [float(b / s) if b else 1.0 for b, s in zip(shares, speed)]
