@@ -34,7 +34,9 @@ template <> struct Elem<uint16_t> { static constexpr int VE = 8; };
 __device__ __forceinline__ u32x4 ld_vec(const void *p)
 {
     const KT_GLOBAL u32x4 *g = (const KT_GLOBAL u32x4 *)p;
-#if KT_NT_LOAD
+#if KT_NT_LOAD == 2
+    return *(const volatile KT_GLOBAL u32x4 *)g;      // system scope (sc0 sc1), for measurement
+#elif KT_NT_LOAD
     return __builtin_nontemporal_load(g);
 #else
     return *g;
@@ -44,11 +46,33 @@ __device__ __forceinline__ u32x4 ld_vec(const void *p)
 __device__ __forceinline__ void st_vec(void *p, u32x4 v)
 {
     KT_GLOBAL u32x4 *g = (KT_GLOBAL u32x4 *)p;
-#if KT_NT_STORE
+#if KT_NT_STORE == 2
+    *(volatile KT_GLOBAL u32x4 *)g = v;                // system scope (sc0 sc1), for measurement
+#elif KT_NT_STORE
     __builtin_nontemporal_store(v, g);
 #else
     *g = v;
 #endif
+}
+
+// Store policy of the kernels that write about as much as they read (pack, unpack, SGD on
+// unpack with bf16 gradients: 44-50 % of their bytes are written): a system-scope store, which
+// the L2 writes through at once instead of holding the line, measured 1-4 points of 8 TB/s
+// better there than the non-temporal store, and 1-3 points worse in the kernels that write a
+// quarter of their bytes or less (reduce, fused pass, K copies -> parameters), which keep
+// st_vec.  KT_WT_STORE=0 builds these kernels with st_vec as well, for measurement.
+#ifndef KT_WT_STORE
+#define KT_WT_STORE 1
+#endif
+template <bool WT> __device__ __forceinline__ void st_vec_copy(void *p, u32x4 v)
+{
+#if KT_WT_STORE && KT_NT_STORE == 1
+    if (WT) {
+        *(volatile KT_GLOBAL u32x4 *)p = v;
+        return;
+    }
+#endif
+    st_vec(p, v);
 }
 
 template <typename T> __device__ __forceinline__ T ld_elem(const T *p) { return *(const KT_GLOBAL T *)p; }

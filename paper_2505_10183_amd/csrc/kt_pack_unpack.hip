@@ -76,7 +76,7 @@ __device__ __forceinline__ void pack_mixed(const V &tv, int nt, const TileGeom &
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
         const int64_t e0 = g.start + (int64_t)((part * VPT + j) * KT_BLOCK + threadIdx.x) * VE;
-        if (how[j] == 1) st_vec(dst + e0, val[j]);
+        if (how[j] == 1) st_vec_copy<true>(dst + e0, val[j]);
         else if (how[j] == 2) pack_slow<T>(tv, nt, e0, b_n, dst);
     }
 }
@@ -123,10 +123,10 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_pack_kernel(KtDeviceTables tb, in
 #pragma unroll
                 for (int j = 0; j < VPT; ++j) r[j] = ld_vec(s4 + (part * VPT + j) * KT_BLOCK + tid);
 #pragma unroll
-                for (int j = 0; j < VPT; ++j) st_vec(d4 + (part * VPT + j) * KT_BLOCK + tid, r[j]);
+                for (int j = 0; j < VPT; ++j) st_vec_copy<true>(d4 + (part * VPT + j) * KT_BLOCK + tid, r[j]);
             } else {
 #pragma unroll 1
-                for (int v = part * KT_BLOCK + tid; v < nvec; v += COPY_SPLIT * KT_BLOCK) st_vec(d4 + v, ld_vec(s4 + v));
+                for (int v = part * KT_BLOCK + tid; v < nvec; v += COPY_SPLIT * KT_BLOCK) st_vec_copy<true>(d4 + v, ld_vec(s4 + v));
             }
             return;
         }
@@ -193,7 +193,7 @@ __device__ __forceinline__ void unpack_mixed(const V &tv, int nt, const TileGeom
     }
 #pragma unroll
     for (int j = 0; j < VPT; ++j) {
-        if (where[j] > 1) st_vec(reinterpret_cast<void *>(where[j]), scale_vec<T>(val[j], scale));
+        if (where[j] > 1) st_vec_copy<true>(reinterpret_cast<void *>(where[j]), scale_vec<T>(val[j], scale));
         else if (where[j] == 1)
             unpack_slow<T>(tv, nt, g.start + (int64_t)((part * VPT + j) * KT_BLOCK + threadIdx.x) * VE, b_n, src, scale);
     }
@@ -236,11 +236,11 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_kernel(KtDeviceTables tb, 
 #pragma unroll
                 for (int j = 0; j < VPT; ++j) r[j] = ld_vec(s4 + (part * VPT + j) * KT_BLOCK + tid);
 #pragma unroll
-                for (int j = 0; j < VPT; ++j) st_vec(d4 + (part * VPT + j) * KT_BLOCK + tid, scale_vec<T>(r[j], scale));
+                for (int j = 0; j < VPT; ++j) st_vec_copy<true>(d4 + (part * VPT + j) * KT_BLOCK + tid, scale_vec<T>(r[j], scale));
             } else {
 #pragma unroll 1
                 for (int v = part * KT_BLOCK + tid; v < nvec; v += COPY_SPLIT * KT_BLOCK)
-                    st_vec(d4 + v, scale_vec<T>(ld_vec(s4 + v), scale));
+                    st_vec_copy<true>(d4 + v, scale_vec<T>(ld_vec(s4 + v), scale));
             }
             return;
         }

@@ -34,8 +34,8 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
                     SgdVec<T>::apply(gr, pr, vr, a);
 #pragma unroll
                     for (int h = 0; h < PV; ++h) {
-                        st_vec(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
-                        st_vec(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
+                        st_vec_copy<sizeof(T) == 2>(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
+                        st_vec_copy<sizeof(T) == 2>(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
                         if (MASTER) st_model_quad(reinterpret_cast<void *>(ma + 8 * h), pr[h]);
                     }
                     continue;
@@ -104,8 +104,8 @@ __device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x
     for (int u = 0; u < QB; ++u) {
         const int idx = (u0 + u) * KT_BLOCK + tid;
         sgd_quad(gr[u], pr[u], vr[u], a);
-        st_vec(p4 + idx, pr[u]);
-        st_vec(v4 + idx, vr[u]);
+        st_vec_copy<sizeof(T) == 2>(p4 + idx, pr[u]);
+        st_vec_copy<sizeof(T) == 2>(v4 + idx, vr[u]);
         if (MASTER) st_model_quad(m2 + idx, pr[u]);
     }
 }
@@ -162,8 +162,8 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
                     u32x4 pr = ld_vec(p4 + idx), vr = u32x4{0, 0, 0, 0};
                     if (!a.first) vr = ld_vec(v4 + idx);
                     sgd_quad(gq, pr, vr, a);
-                    st_vec(p4 + idx, pr);
-                    st_vec(v4 + idx, vr);
+                    st_vec_copy<sizeof(T) == 2>(p4 + idx, pr);
+                    st_vec_copy<sizeof(T) == 2>(v4 + idx, vr);
                     if (MASTER) st_model_quad(m2 + idx, pr);
                 }
             }
