@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_sgd_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip",
                   "kt_sgd.hip", "kt_fused_sgd.hip")
-TRAFFIC_SOURCES_SHA = "1cf772aec39a2800"
-TRAFFIC_BYTES = {"decoder_1p3b": 23704848624, "vit_b16": 3119141350}
+TRAFFIC_SOURCES_SHA = "603d79b93f773830"
+TRAFFIC_BYTES = {"decoder_1p3b": 23704808473, "vit_b16": 3119133794}
 
 
 def measured_traffic(workload):

@@ -36,7 +36,7 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
                     for (int h = 0; h < PV; ++h) {
                         st_vec_copy<sizeof(T) == 2>(reinterpret_cast<u32x4 *>(pa) + h, pr[h]);
                         st_vec_copy<sizeof(T) == 2>(reinterpret_cast<u32x4 *>(va) + h, vr[h]);
-                        if (MASTER) st_model_quad(reinterpret_cast<void *>(ma + 8 * h), pr[h]);
+                        if (MASTER) st_model_quad<true>(reinterpret_cast<void *>(ma + 8 * h), pr[h]);
                     }
                     continue;
                 }
@@ -106,7 +106,7 @@ __device__ __forceinline__ void sgd_full_tile(const T *src_tile, u32x4 *p4, u32x
         sgd_quad(gr[u], pr[u], vr[u], a);
         st_vec_copy<sizeof(T) == 2>(p4 + idx, pr[u]);
         st_vec_copy<sizeof(T) == 2>(v4 + idx, vr[u]);
-        if (MASTER) st_model_quad(m2 + idx, pr[u]);
+        if (MASTER) st_model_quad<true>(m2 + idx, pr[u]);
     }
 }
 
@@ -164,7 +164,7 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_unpack_sgd_kernel(KtDeviceTables 
                     sgd_quad(gq, pr, vr, a);
                     st_vec_copy<sizeof(T) == 2>(p4 + idx, pr);
                     st_vec_copy<sizeof(T) == 2>(v4 + idx, vr);
-                    if (MASTER) st_model_quad(m2 + idx, pr);
+                    if (MASTER) st_model_quad<true>(m2 + idx, pr);
                 }
             }
             return;

@@ -65,11 +65,18 @@ __device__ __forceinline__ void sgd_quad(const Quad<uint16_t> &g, u32x4 &p, u32x
 
 // Mixed precision: the four updated binary32 master values of a quad are also
 // written, rounded to nearest-even, as four bf16 model parameters (8 bytes).
-__device__ __forceinline__ void st_model_quad(void *m, u32x4 p)
+// SYS: system-scope store (SGD on unpack: +1-2 points of 8 TB/s), else non-temporal.
+template <bool SYS = false> __device__ __forceinline__ void st_model_quad(void *m, u32x4 p)
 {
     u32x2 o;
     o[0] = f32_to_bf16(__uint_as_float(p[0])) | (f32_to_bf16(__uint_as_float(p[1])) << 16);
     o[1] = f32_to_bf16(__uint_as_float(p[2])) | (f32_to_bf16(__uint_as_float(p[3])) << 16);
+#if KT_WT_STORE && KT_NT_STORE == 1
+    if (SYS) {
+        *(volatile KT_GLOBAL u32x2 *)m = o;
+        return;
+    }
+#endif
     __builtin_nontemporal_store(o, (KT_GLOBAL u32x2 *)m);
 }
 
