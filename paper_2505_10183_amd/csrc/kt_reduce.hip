@@ -35,6 +35,12 @@
 #ifndef KT_REDUCE_CHUNK
 #define KT_REDUCE_CHUNK 0
 #endif
+//   KT_REDUCE_LD_AUX  -1: the loads of a full tile are non-temporal global loads
+//                     a >= 0: buffer loads through a descriptor of the tile (16 KiB per copy)
+//                        with cache-policy bits a (1 = sc0, 2 = nt, 16 = sc1), for measurement
+#ifndef KT_REDUCE_LD_AUX
+#define KT_REDUCE_LD_AUX -1
+#endif
 
 namespace {
 
@@ -115,7 +121,17 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
 #endif
     if (nvec == KT_TILE_VECS) {
         u32x4 r[VPT][K];
-#if KT_REDUCE_ISSUE == 1
+#if KT_REDUCE_LD_AUX >= 0
+        __amdgpu_buffer_rsrc_t rs[K];
+#pragma unroll
+        for (int k = 0; k < K; ++k)
+            rs[k] = __builtin_amdgcn_make_buffer_rsrc(const_cast<T *>(x[k]), 0, KT_TILE_BYTES, 0x00020000);
+#pragma unroll
+        for (int u = 0; u < VPT; ++u)
+#pragma unroll
+            for (int k = 0; k < K; ++k)
+                r[u][k] = __builtin_amdgcn_raw_buffer_load_b128(rs[k], reduce_vec_index(u, tid) * 16, 0, KT_REDUCE_LD_AUX);
+#elif KT_REDUCE_ISSUE == 1
 #pragma unroll
         for (int k = 0; k < K; ++k)
 #pragma unroll
