@@ -67,8 +67,8 @@ __device__ __forceinline__ void sgd_mixed(const V &tv, int nt, const TileGeom &g
 // lane, all loaded before the first store.  The smaller the share the better
 // here, unlike in the read-dominated reduce: with one quad per lane (a
 // workgroup reads 4 KiB of p and of v and writes the same 4 KiB back at once)
-// the kernel runs at 76 % (bf16) and 78 % (fp32) of 8 TB/s, with 4 quads at
-// 70 % and 73 %.  KT_SGD_QB overrides the default for measurement.
+// the kernel runs at 79 % of 8 TB/s for either gradient type, with 2 quads
+// at 75 % (bf16) and 78 % (fp32).  KT_SGD_QB overrides the default for measurement.
 #ifndef KT_SGD_QB
 #define KT_SGD_QB 1
 #endif
