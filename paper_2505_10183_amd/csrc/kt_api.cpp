@@ -66,6 +66,39 @@ static bool capturing(hipStream_t s)
         return KT_EINVAL;                                              \
     }
 
+// ---- store window ------------------------------------------------------------
+
+// KT_WINDOW_NS: period in nanoseconds (0 switches the window off); KT_WINDOW_OPEN_PCT: the share
+// of the period in which stores are issued.
+#ifndef KT_WINDOW_NS
+#define KT_WINDOW_NS 12000
+#endif
+#ifndef KT_WINDOW_OPEN_PCT
+#define KT_WINDOW_OPEN_PCT 10
+#endif
+
+KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles)
+{
+    KtWindow off{0, 0};
+    if (KT_WINDOW_NS <= 0 || K < 4 || ntiles < min_tiles) return off;
+    // rate of the device-wide constant clock in kHz, looked up once per device
+    static std::atomic<int> rate_khz[64];
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return off;
+    int r = rate_khz[dev].load(std::memory_order_relaxed);
+    if (r == 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeWallClockRate, dev) != hipSuccess || v <= 0) v = -1;
+        rate_khz[dev].store(v, std::memory_order_relaxed);
+        r = v;
+    }
+    if (r <= 0) { (void)hipGetLastError(); return off; }
+    const uint64_t period = (uint64_t)r * KT_WINDOW_NS / 1000000;     // ticks
+    const uint64_t width = period * KT_WINDOW_OPEN_PCT / 100;
+    if (period < 64 || period > (1u << 30) || width < 1) return off;
+    return KtWindow{(uint32_t)period, (uint32_t)width};
+}
+
 // ---- plan object -----------------------------------------------------------
 
 // A per-call table of device pointers (tensor/bucket or peer/out pointers)

@@ -75,6 +75,20 @@ template <bool WT> __device__ __forceinline__ void st_vec_copy(void *p, u32x4 v)
     st_vec(p, v);
 }
 
+// Holds a wave back until the store window opens (KtWindow).  Bounded twice over: the clock
+// always advances, so the condition comes true within one period (about 12 us), and the
+// iteration count ends the loop in any case.  (The low 32 bits of the clock wrap every 43 s at
+// 100 MHz; one period is then irregular.)
+__device__ __forceinline__ void kt_wait_store_window(const KtWindow &w)
+{
+    if (w.width) {
+        for (int spin = 0; spin < 4096; ++spin) {
+            if ((uint32_t)wall_clock64() % w.period < w.width) break;
+            __builtin_amdgcn_s_sleep(4);
+        }
+    }
+}
+
 template <typename T> __device__ __forceinline__ T ld_elem(const T *p) { return *(const KT_GLOBAL T *)p; }
 template <typename T> __device__ __forceinline__ void st_elem(T *p, T v) { *(KT_GLOBAL T *)p = v; }
 

@@ -94,7 +94,7 @@ template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, int64_t tile0,
                                                             const void *const *local_ptrs,
                                                             const void *const *peer_ptrs, KtWeights wts,
-                                                            float scale, void *const *out_ptrs)
+                                                            float scale, void *const *out_ptrs, KtWindow win)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
@@ -131,14 +131,18 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_kernel(KtDeviceTables tb, i
                     for (int k = 1; k < K; ++k)
                         r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k - 1]) + v0 + u * KT_BLOCK);
                 }
+                u32x4 res[VPT];
 #pragma unroll
                 for (int u = 0; u < VPT; ++u) {
                     Acc<T> acc;
                     acc.first(r[u][0], w[0]);
 #pragma unroll
                     for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
-                    st_vec(reinterpret_cast<u32x4 *>(dst) + v0 + u * KT_BLOCK, scale_vec<T>(acc.finish(), scale));
+                    res[u] = scale_vec<T>(acc.finish(), scale);
                 }
+                kt_wait_store_window(win);     // large launches: the chip writes in bursts (KtWindow)
+#pragma unroll
+                for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(dst) + v0 + u * KT_BLOCK, res[u]);
             } else {
 #pragma unroll 1
                 for (int v = part * KT_BLOCK + tid; v < nvec; v += SPLIT * KT_BLOCK) {
@@ -214,7 +218,8 @@ template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables tb, int64_t tile0,
                                                                   const void *const *local_ptrs,
                                                                   const void *const *peer_ptrs, int K,
-                                                                  KtWeights wts, float scale, void *const *out_ptrs)
+                                                                  KtWeights wts, float scale, void *const *out_ptrs,
+                                                                  KtWindow win)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
@@ -234,9 +239,12 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_fused_manyk_kernel(KtDeviceTables
             Acc<T> acc[VPT];
             sum_in_chunks<T, DEVW>(acc, [&](int k) { return k == 0 ? src : reinterpret_cast<const T *>(pp[k - 1]) + g.start; },
                              wts, K, tid);
+            u32x4 res[VPT];
 #pragma unroll
-            for (int u = 0; u < VPT; ++u)
-                st_vec(reinterpret_cast<u32x4 *>(dst) + u * KT_BLOCK + tid, scale_vec<T>(acc[u].finish(), scale));
+            for (int u = 0; u < VPT; ++u) res[u] = scale_vec<T>(acc[u].finish(), scale);
+            kt_wait_store_window(win);
+#pragma unroll
+            for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(dst) + u * KT_BLOCK + tid, res[u]);
             return;
         }
     }
@@ -288,8 +296,10 @@ hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntile
         kt_fused_elem_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
         return hipGetLastError();
     }
+    // the window assumes one workgroup per tile (the time a generation of workgroups reads for)
+    const KtWindow win = FUSED_SPLIT == 1 ? kt_store_window(K, ntiles, KT_WINDOW_MIN_TILES_FUSED) : KtWindow{0, 0};
     if (K > 8) {
-        kt_fused_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs);
+        kt_fused_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, locals, peers, K, w, scale, outs, win);
         return hipGetLastError();
     }
     // FUSED_SPLIT workgroups per tile; a grid may not hold 2^32 or more lanes: very large plans go in several launches
@@ -300,7 +310,7 @@ hipError_t launch_fused_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntile
         const int64_t t0 = tile0 + done;
         switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_fused_kernel<T, KK, DEVW><<<g2, block, 0, s>>>(tb, t0, locals, peers, w, scale, outs); break;
+    case KK: kt_fused_kernel<T, KK, DEVW><<<g2, block, 0, s>>>(tb, t0, locals, peers, w, scale, outs, win); break;
             KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
         default: return hipErrorInvalidValue;

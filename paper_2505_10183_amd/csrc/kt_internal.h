@@ -69,6 +69,32 @@ int kt_launch_unpack(const KtDeviceTables &tb, kt_dtype dt, int64_t tile0,
                      int64_t ntiles, const void *const *d_bucket_ptrs,
                      float scale, void *const *d_tensor_ptrs, bool vector_ok,
                      void *stream);
+// Store window of the read-dominated kernels (reduce, fused pass) on large launches: every wave
+// holds its finished results back until the device-wide constant-rate clock, masked to a period
+// of about 10 us, is inside the first `width` ticks, so that the whole chip alternates between
+// reading and writing instead of sprinkling one written line among eight read ones.  Measured on
+// 8 peers: 72-73 % -> 77-78 % of 8 TB/s, flat for periods of 9-18 us, and a steep loss once the
+// period exceeds the time the resident workgroups need for their loads (about 14-19 us), which
+// is why it is used only where that time is known to be longer (K >= 4, many tiles).
+// width == 0: no window.
+struct KtWindow {
+    uint32_t period;  // clock ticks
+    uint32_t width;   // ticks at the start of each period in which stores are issued
+};
+// The window for a launch of `ntiles` tiles with K peers on the current device (host); none
+// below `min_tiles` tiles: a launch of a few generations of workgroups only pays for the waits
+// of its first and last one.
+KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles);
+// Smallest launches that use the window.  The fused pass is a step of its own and gains from
+// 16 Ki tiles (256 MiB per copy) on; the reduce inside the chained step (between pack and
+// unpack) measured 2 % slower with the window at 21 Ki tiles and 5 % faster at 160 Ki.
+#ifndef KT_WINDOW_MIN_TILES_FUSED
+#define KT_WINDOW_MIN_TILES_FUSED 16384
+#endif
+#ifndef KT_WINDOW_MIN_TILES_REDUCE
+#define KT_WINDOW_MIN_TILES_REDUCE 65536
+#endif
+
 // The K weights of a launch travel in the kernel-argument block (`w`), unless
 // `dev` is set: then the kernels read them from that device array when they
 // run (kt_plan_set_weights), so that a recorded graph follows later updates.

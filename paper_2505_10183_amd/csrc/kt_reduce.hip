@@ -68,7 +68,7 @@ __device__ __forceinline__ int reduce_vec_index(int u, int tid)
 template <typename T, int K, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDeviceTables tb, int64_t tile0,
                                                              const void *const *peer_ptrs, KtWeights wts,
-                                                             void *const *out_ptrs)
+                                                             void *const *out_ptrs, KtWindow win)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
@@ -115,6 +115,7 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
                 for (int c = 0; c < (int)(sizeof(acc[u].a) / sizeof(float)); ++c) asm volatile("" : "+v"(acc[u].a[c]));
             __builtin_amdgcn_sched_barrier(0);
         }
+        kt_wait_store_window(win);
 #pragma unroll
         for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc[u].finish());
     } else
@@ -144,14 +145,18 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
             for (int k = 0; k < K; ++k)
                 r[u][k] = ld_vec(reinterpret_cast<const u32x4 *>(x[k]) + reduce_vec_index(u, tid));
 #endif
+        u32x4 res[VPT];
 #pragma unroll
         for (int u = 0; u < VPT; ++u) {
             Acc<T> acc;
             acc.first(r[u][0], w[0]);
 #pragma unroll
             for (int k = 1; k < K; ++k) acc.add(r[u][k], w[k]);
-            st_vec(reinterpret_cast<u32x4 *>(out) + reduce_vec_index(u, tid), acc.finish());
+            res[u] = acc.finish();
         }
+        kt_wait_store_window(win);     // large launches: the chip writes in bursts (KtWindow)
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + reduce_vec_index(u, tid), res[u]);
     } else {
         for (int v = tid; v < nvec; v += KT_BLOCK) {
             u32x4 r[K];
@@ -178,7 +183,7 @@ __global__ __launch_bounds__(KT_BLOCK) KT_REDUCE_OCC void kt_reduce_kernel(KtDev
 template <typename T, bool DEVW>
 __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTables tb, int64_t tile0,
                                                                    const void *const *peer_ptrs, int K,
-                                                                   KtWeights wts, void *const *out_ptrs)
+                                                                   KtWeights wts, void *const *out_ptrs, KtWindow win)
 {
     constexpr int VE = Elem<T>::VE;
     constexpr int64_t TILE_ELEMS = (int64_t)KT_TILE_VECS * VE;
@@ -193,8 +198,12 @@ __global__ __launch_bounds__(KT_BLOCK) void kt_reduce_manyk_kernel(KtDeviceTable
     if (nvec == KT_TILE_VECS) {
         Acc<T> acc[VPT];
         sum_in_chunks<T, DEVW>(acc, [&](int k) { return reinterpret_cast<const T *>(pp[k]) + g.start; }, wts, K, tid);
+        u32x4 res[VPT];
 #pragma unroll
-        for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, acc[u].finish());
+        for (int u = 0; u < VPT; ++u) res[u] = acc[u].finish();
+        kt_wait_store_window(win);
+#pragma unroll
+        for (int u = 0; u < VPT; ++u) st_vec(reinterpret_cast<u32x4 *>(out) + u * KT_BLOCK + tid, res[u]);
         return;
     }
     // the ragged last tile of a bucket: one vector at a time
@@ -243,12 +252,13 @@ hipError_t launch_reduce_t(const KtDeviceTables &tb, int64_t tile0, int64_t ntil
         kt_reduce_elem_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs);
         return hipGetLastError();
     }
+    const KtWindow win = kt_store_window(K, ntiles, KT_WINDOW_MIN_TILES_REDUCE);
     switch (K) {
 #define KT_CASE(KK) \
-    case KK: kt_reduce_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs); break;
+    case KK: kt_reduce_kernel<T, KK, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, w, outs, win); break;
         KT_CASE(1) KT_CASE(2) KT_CASE(3) KT_CASE(4) KT_CASE(5) KT_CASE(6) KT_CASE(7) KT_CASE(8)
 #undef KT_CASE
-    default: kt_reduce_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs); break;
+    default: kt_reduce_manyk_kernel<T, DEVW><<<grid, block, 0, s>>>(tb, tile0, peers, K, w, outs, win); break;
     }
     return hipGetLastError();
 }
