@@ -55,7 +55,7 @@ def setup(name, dev, in_place=True, misalign=False):
     import paper_2505_10183_amd as kt
     from paper_2505_10183_amd import workloads as wl
 
-    w = wl.WORKLOADS[name]
+    w = wl.get(name)
     K = w.K
     plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)
     shares, weights = kt.kt_plan_shares(w.throughputs, w.global_batch)
@@ -223,7 +223,7 @@ def time_workload(name, steps, warmup, dev, in_place=True, misalign=False, event
 
 def wl_total(name):
     from paper_2505_10183_amd import workloads as wl
-    return wl.WORKLOADS[name].total_elems
+    return wl.get(name).total_elems
 
 
 def host_threads():
@@ -310,7 +310,7 @@ def two_level(dev, name="vit_b16", reps=5):
     import torch
     import paper_2505_10183_amd as kt
     from paper_2505_10183_amd import workloads as wl
-    w = wl.WORKLOADS[name]
+    w = wl.get(name)
     K, G = w.K, 2
     group_of = [0] * (K // 2) + [1] * (K - K // 2)
     plan = kt.Plan(w.numels, w.dtype, w.bucket_cap_bytes, ALIGN_BYTES)

@@ -134,6 +134,26 @@ WORKLOADS = {
 WORKLOAD_ORDER = ("mlp", "resnet18", "mobilenetv2", "vit_b16", "decoder_1p3b")
 
 
+def sized_workload(name: str) -> Workload:
+    """`sized_<dtype>_<tiles>`: 24 equal tensors that fill `tiles` 16 KiB tiles per peer, K = 8,
+    25 MiB (f32) or 64 MiB (bf16) buckets: gradient sets of any size for measurements that depend
+    on the launch size."""
+    _, dtype, tiles = name.split("_")
+    es = 4 if dtype == "f32" else 2
+    n = int(tiles) * (16384 // es)
+    return Workload(name, dtype, tuple(((n // 24),) for _ in range(24)), (1.0, 1.0, 0.8, 0.8, 0.6, 0.6, 0.4, 0.4),
+                    1024, (25 if dtype == "f32" else 64) * MiB, 1e-3, 99)
+
+
+def get(name: str) -> Workload:
+    """A named workload of the table, or a `sized_<dtype>_<tiles>` one."""
+    if name in WORKLOADS:
+        return WORKLOADS[name]
+    if name.startswith("sized_"):
+        return sized_workload(name)
+    raise KeyError(name)
+
+
 def ragged_workload(name: str = "ragged", dtype: str = "f32", K: int = 3,
                     seed: int = 7, n_tensors: int = 40,
                     cap_bytes: int = 96 * 1024) -> Workload:
