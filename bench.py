@@ -32,8 +32,8 @@ HBM_PEAK_GBS = 8000.0
 # sources the figure is reported as null until the counters are taken again.
 KERNEL_SOURCES = ("kt_internal.h", "kt_device.h", "kt_sgd_device.h", "kt_pack_unpack.hip", "kt_reduce.hip", "kt_fused.hip",
                   "kt_sgd.hip", "kt_fused_sgd.hip")
-TRAFFIC_SOURCES_SHA = "f92c06c2167bd6ce"
-TRAFFIC_BYTES = {"decoder_1p3b": 23705640243, "vit_b16": 3119152850}
+TRAFFIC_SOURCES_SHA = "380d6c1e6ad918bb"
+TRAFFIC_BYTES = {"decoder_1p3b": 23705640787, "vit_b16": 3119150390}
 
 
 def measured_traffic(workload):

@@ -68,15 +68,6 @@ static bool capturing(hipStream_t s)
 
 // ---- store window ------------------------------------------------------------
 
-// KT_WINDOW_NS: period in nanoseconds (0 switches the window off); KT_WINDOW_OPEN_PCT: the share
-// of the period in which stores are issued.
-#ifndef KT_WINDOW_NS
-#define KT_WINDOW_NS 12000
-#endif
-#ifndef KT_WINDOW_OPEN_PCT
-#define KT_WINDOW_OPEN_PCT 10
-#endif
-
 KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles)
 {
     KtWindow off{0, 0};

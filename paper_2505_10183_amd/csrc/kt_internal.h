@@ -85,6 +85,14 @@ struct KtWindow {
 // below `min_tiles` tiles: a launch of a few generations of workgroups only pays for the waits
 // of its first and last one.
 KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles);
+// KT_WINDOW_NS: period in nanoseconds (0 switches the window off); KT_WINDOW_OPEN_PCT: the share
+// of the period in which stores are issued.
+#ifndef KT_WINDOW_NS
+#define KT_WINDOW_NS 12000
+#endif
+#ifndef KT_WINDOW_OPEN_PCT
+#define KT_WINDOW_OPEN_PCT 10
+#endif
 // Smallest launches that use the window.  The fused pass is a step of its own and gains from
 // 16 Ki tiles (256 MiB per copy) on; the reduce inside the chained step (between pack and
 // unpack) measured 2 % slower with the window at 21 Ki tiles and 5 % faster at 160 Ki.
