@@ -48,6 +48,12 @@
  *    weight_decay with kt_plan_set_sgd.
  *    A recorded first_step != 0 would reset the momentum on every replay, so
  *    the SGD calls refuse it under capture (KT_EUNSUPPORTED).
+ *  - Large launches (K >= 4, hundreds of MiB per peer) of kt_weighted_reduce and
+ *    kt_fused_step issue their stores in bursts that every workgroup times by
+ *    the device-wide clock (1.2 us in every 12 us), which the memory system
+ *    rewards when the launch has the GPU to itself.  The environment variable
+ *    KT_STORE_WINDOW_NS, read once per process, sets the period in nanoseconds;
+ *    0 switches the bursts off.  Results do not depend on it.
  *  - Streams passed to device calls should outlive the plan.  If the stream of
  *    an earlier call has been destroyed, the library waits for the whole
  *    device instead of that stream when it recycles a pointer table.

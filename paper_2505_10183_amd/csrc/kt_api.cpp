@@ -5,6 +5,7 @@
 #include <atomic>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -68,10 +69,25 @@ static bool capturing(hipStream_t s)
 
 // ---- store window ------------------------------------------------------------
 
+// The period in nanoseconds: KT_WINDOW_NS, or what the environment variable KT_STORE_WINDOW_NS
+// says (read once; 0 switches the windows off, e.g. when other work shares the GPU).
+static long window_ns()
+{
+    static const long ns = [] {
+        const char *e = getenv("KT_STORE_WINDOW_NS");
+        if (!e || !*e) return (long)KT_WINDOW_NS;
+        char *end = nullptr;
+        const long v = strtol(e, &end, 10);
+        return (end && *end == 0 && v >= 0 && v <= 1000000) ? v : (long)KT_WINDOW_NS;
+    }();
+    return ns;
+}
+
 KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles)
 {
     KtWindow off{0, 0};
-    if (KT_WINDOW_NS <= 0 || K < 4 || ntiles < min_tiles) return off;
+    const long ns = window_ns();
+    if (ns <= 0 || K < 4 || ntiles < min_tiles) return off;
     // rate of the device-wide constant clock in kHz, looked up once per device
     static std::atomic<int> rate_khz[64];
     int dev = -1;
@@ -84,7 +100,7 @@ KtWindow kt_store_window(int K, int64_t ntiles, int64_t min_tiles)
         r = v;
     }
     if (r <= 0) { (void)hipGetLastError(); return off; }
-    const uint64_t period = (uint64_t)r * KT_WINDOW_NS / 1000000;     // ticks
+    const uint64_t period = (uint64_t)r * (uint64_t)ns / 1000000;     // ticks
     const uint64_t width = period * KT_WINDOW_OPEN_PCT / 100;
     if (period < 64 || period > (1u << 30) || width < 1) return off;
     return KtWindow{(uint32_t)period, (uint32_t)width};

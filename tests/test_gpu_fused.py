@@ -112,3 +112,18 @@ def test_fused_tiny_and_many_tensors():
 @pytest.mark.parametrize("name", ["mlp", "mobilenetv2", "resnet18", "vit_b16"])
 def test_fused_workloads(name):
     run_case(wl.WORKLOADS[name], 16, 1.0)
+
+
+def test_store_windows_can_be_switched_off():
+    """KT_STORE_WINDOW_NS=0 in the environment (read once per process) switches the store windows of
+    large launches off; results are the same either way.  Runs the ViT-B/16 case, whose fused pass is
+    large enough to use a window, in a child process with the variable set."""
+    import os
+    import subprocess
+    env = dict(os.environ, KT_STORE_WINDOW_NS="0")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "gpu", "-p", "no:cacheprovider",
+                        os.path.join(root, "tests", "test_gpu_fused.py"), "-k", "test_fused_workloads and vit_b16"],
+                       cwd=root, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
+    assert "1 passed" in r.stdout, r.stdout[-500:]

@@ -501,6 +501,31 @@ def test_pointer_churn_and_streams():
         assert all(bool((t == float(r)).all()) for t in o2)
 
 
+@pytest.mark.parametrize("dtype,K", [("f32", 5), ("bf16", 4)])
+def test_reduce_large_launch_with_store_windows(dtype, K):
+    """A launch large enough (65 536 tiles, K >= 4) for the reduce to hold its stores back until the
+    chip-wide store window: every element of every bucket against the checker's strict mode, in place
+    and into separate outputs."""
+    w = wl.get("sized_%s_65536" % dtype)
+    plan = kt.Plan(w.numels, dtype, w.bucket_cap_bytes, 16)
+    nb, elems = plan.num_buckets, plan.bucket_elems()
+    assert plan.num_tiles >= 65536
+    thr = w.throughputs[:K]
+    shares, weights = kt.kt_plan_shares(thr, 1024)
+    wts = oracle.share_weights(oracle.plan_shares(thr, 1024), 1024)
+    peers = [[wl.flat_normal(n, dtype, 1e-3, 3000 + 50 * k + b, DEV) for b, n in enumerate(elems)] for k in range(K)]
+    hp0 = [host(peers[0][b]) for b in range(nb)]
+    outs = [torch.empty_like(t) for t in peers[0]]
+    flat = [peers[k][b] for b in range(nb) for k in range(K)]
+    plan.kt_weighted_reduce(-1, flat, K, weights, outs)
+    plan.kt_weighted_reduce(-1, flat, K, weights, peers[0])          # in place over peer 0
+    torch.cuda.synchronize()
+    for b in range(nb):
+        want = oracle.weighted_reduce([hp0[b]] + [host(peers[k][b]) for k in range(1, K)], wts, dtype, "S")
+        assert raw(host(outs[b])).tobytes() == raw(want).tobytes(), ("own output", b)
+        assert raw(host(peers[0][b])).tobytes() == raw(want).tobytes(), ("in place", b)
+
+
 def test_two_host_threads_share_a_plan():
     """Two host threads, each with a stream of its own, call into one plan at
     the same time with pointer sets of their own (the library serialises calls
